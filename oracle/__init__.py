@@ -1,0 +1,6 @@
+"""CPU oracle of the QaRL low-bit MoE hot path: TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this
+package.  It shares no code with the HIP library.
+"""
+from .oracle import *  # noqa: F401,F403

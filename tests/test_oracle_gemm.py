@@ -1,0 +1,130 @@
+"""Pins of the oracle's quantized GEMMs (paper eq. (1), eq. (2)), SiLU product and combine."""
+import numpy as np
+import scipy.special
+import torch
+
+from paper_2604_07853_amd import synth
+
+
+def _quant(oracle, E, N, K, seed):
+    w = synth.normal_bf16((E, N, K), 0.02, seed)
+    return oracle.quantize_int4(synth.bits(w))
+
+
+def test_one_hot_probe_exposes_dequantized_weight(oracle):
+    codes, scales = _quant(oracle, 2, 24, 256, seed=1)
+    eye = synth.bits(torch.eye(256).to(torch.bfloat16))
+    x = np.concatenate([eye, eye])
+    off = np.array([0, 256, 512], dtype=np.int32)
+    y = oracle.qgemm_w4a16(x, codes, scales, off)
+    deq = oracle.dequant_int4(codes, scales).astype(np.float64)
+    assert np.array_equal(y[:256], deq[0].T) and np.array_equal(y[256:], deq[1].T)
+    q = oracle.unpack_int4(codes).astype(np.float64)
+    s = np.repeat(oracle.bf16_to_f64(scales), 128, axis=2)
+    assert np.array_equal(deq, q * s)
+
+
+def test_exact_integer_regime_equals_integer_matmul(oracle):
+    rng = np.random.default_rng(7)
+    E, N, K, M = 3, 40, 384, 29
+    q = rng.integers(-7, 8, size=(E, N, K))
+    q[:, :, ::128] = 7
+    e = rng.integers(-3, 2, size=(E, N, K // 128))
+    w = q * np.repeat(2.0 ** e, 128, axis=2)
+    codes, scales = oracle.quantize_int4(synth.bits(torch.tensor(w, dtype=torch.float32).to(torch.bfloat16)))
+    assert np.array_equal(oracle.unpack_int4(codes), q.astype(np.int8))
+    xi = rng.integers(-4, 5, size=(M, K))
+    x = synth.bits(torch.tensor(xi, dtype=torch.float32).to(torch.bfloat16))
+    off = np.array([0, 10, 10, 29], dtype=np.int32)          # expert 1 is empty
+    rm = rng.permutation(M).astype(np.int32)
+    for acc32 in (False, True):
+        y = oracle.qgemm_w4a16(x, codes, scales, off, rm, acc32=acc32)
+        for ex, (lo, hi) in enumerate(zip(off[:-1], off[1:])):
+            # scaled by 8 everything is an integer: exact reference in int64
+            wi = (w[ex] * 8).astype(np.int64)
+            want = xi[rm[lo:hi]].astype(np.int64) @ wi.T
+            assert np.array_equal(y[lo:hi] * 8, want.astype(np.float64))
+
+
+def test_general_data_matches_numpy_matmul_and_noise_floor(oracle):
+    E, N, K, M = 2, 48, 512, 33
+    codes, scales = _quant(oracle, E, N, K, seed=3)
+    x = synth.bits(synth.normal_bf16((M, K), 1.0, seed=4))
+    off = np.array([0, 20, 33], dtype=np.int32)
+    y = oracle.qgemm_w4a16(x, codes, scales, off)
+    q = oracle.unpack_int4(codes).astype(np.float64)               # python-side unpack
+    s = np.repeat(oracle.bf16_to_f64(scales), 128, axis=2)
+    xf = oracle.bf16_to_f64(x)
+    want = np.concatenate([xf[:20] @ (q[0] * s[0]).T, xf[20:] @ (q[1] * s[1]).T])
+    assert np.allclose(y, want, rtol=1e-12, atol=1e-13)
+    y32 = oracle.qgemm_w4a16(x, codes, scales, off, acc32=True)
+    rel = np.abs(y32 - y).max() / np.sqrt((y ** 2).mean())
+    assert 0 < rel < 2e-6                                          # fp32 order noise, K=512
+
+
+def test_fp8_gemm_matches_numpy(oracle):
+    E, N, K, M = 2, 32, 256, 17
+    wq, sw = oracle.quantize_fp8_rows(synth.bits(synth.normal_bf16((E, N, K), 0.02, seed=5)))
+    xq, sx = oracle.quantize_fp8_rows(synth.bits(synth.normal_bf16((M, K), 1.0, seed=6)))
+    off = np.array([0, 9, 17], dtype=np.int32)
+    y = oracle.qgemm_fp8(xq, sx, wq, sw, off)
+    xd = torch.from_numpy(xq).view(torch.float8_e4m3fn).double().numpy()
+    wd = torch.from_numpy(wq).view(torch.float8_e4m3fn).double().numpy()
+    want = np.concatenate([(xd[:9] @ wd[0].T) * sx[:9, None] * sw[0][None, :],
+                           (xd[9:] @ wd[1].T) * sx[9:, None] * sw[1][None, :]])
+    assert np.allclose(y, want, rtol=1e-12)
+    # one-hot probe: x rows = 448*e_k -> s_x = 1 exactly, output = s_w * decode(w_q)
+    eye = synth.bits((torch.eye(K) * 448).to(torch.bfloat16))
+    xq1, sx1 = oracle.quantize_fp8_rows(eye)
+    assert np.all(sx1 == 1.0)
+    y1 = oracle.qgemm_fp8(xq1, sx1, wq[:1], sw[:1], np.array([0, K], dtype=np.int32))
+    assert np.array_equal(y1, (wd[0] * 448.0 * sw[0][:, None].astype(np.float64)).T)
+
+
+def test_silu_mul_and_combine(oracle):
+    gu = np.array([[0.0, 50.0, -50.0, 1.0, 3.0, 2.0, 2.0, -1.5]])  # I = 4
+    a, ex = oracle.silu_mul(gu)
+    assert ex[0, 0] == 0.0
+    assert np.isclose(ex[0, 1], 100.0, rtol=1e-15)                 # silu(g) -> g for large g
+    assert abs(ex[0, 2]) < 1e-19                                   # silu(g) -> 0 for large -g
+    assert np.isclose(ex[0, 3], -1.5 / (1 + np.e ** -1.0))
+    rng = np.random.default_rng(1)
+    gu = rng.normal(size=(7, 64)) * 3
+    a, ex = oracle.silu_mul(gu)
+    want = gu[:, :32] * scipy.special.expit(gu[:, :32]) * gu[:, 32:]
+    assert np.allclose(ex, want, rtol=1e-13)
+    assert np.array_equal(a, synth.bits(torch.tensor(ex).to(torch.bfloat16)))
+    # combine: k = 1 is a permuted copy; equal weights give the mean
+    y = rng.normal(size=(6, 5))
+    pairs = np.array([3, 1, 0, 5, 4, 2], dtype=np.int32)
+    out, _ = oracle.combine(y, pairs, np.ones((6, 1)), 6, 1)
+    assert np.array_equal(out[pairs], y)
+    out, ob = oracle.combine(y, pairs, np.full((2, 3), 1 / 3), 2, 3)
+    inv = np.argsort(pairs)
+    assert np.allclose(out[0], y[inv[:3]].mean(axis=0)) and np.allclose(out[1], y[inv[3:]].mean(axis=0))
+    assert np.array_equal(ob, synth.bits(torch.tensor(out).to(torch.bfloat16)))
+
+
+def test_moe_layer_matches_dense_torch_reference(oracle):
+    """The whole W4A16 layer against a dense float64 torch evaluation that never groups
+    tokens: out[t] = sum_j w_j * down_e(silu(gate_e x) * up_e x) with a bf16-rounded product."""
+    E, Hh, Ii, T, k = 8, 256, 128, 20, 3
+    gu, dn = synth.expert_weights(E, Hh, Ii, seed=10)
+    guc, gus = oracle.quantize_int4(synth.bits(gu))
+    dnc, dns = oracle.quantize_int4(synth.bits(dn))
+    x = synth.normal_bf16((T, Hh), 1.0, seed=11)
+    lg = synth.router_logits(T, E, seed=12)
+    res = oracle.moe_ffn_w4a16(synth.bits(x), synth.bits(lg), guc, gus, dnc, dns, topk=k)
+    Wgu = torch.tensor(oracle.dequant_int4(guc, gus)).double()
+    Wdn = torch.tensor(oracle.dequant_int4(dnc, dns)).double()
+    p = torch.softmax(lg.double(), dim=1)
+    out = torch.zeros(T, Hh, dtype=torch.float64)
+    for t in range(T):
+        ids = res["ids"][t]
+        wsel = p[t, ids.tolist()]
+        wsel = wsel / wsel.sum()
+        for j, e in enumerate(ids):
+            z = Wgu[e] @ x[t].double()
+            a = (torch.nn.functional.silu(z[:Ii]) * z[Ii:]).to(torch.bfloat16).double()
+            out[t] += wsel[j] * (Wdn[e] @ a)
+    assert np.allclose(res["out"], out.numpy(), rtol=1e-9, atol=1e-12)
