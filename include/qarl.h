@@ -1,0 +1,155 @@
+/*
+ * qarl.h -- C ABI of the MI355X (gfx950) hot path of QaRL: the low-bit quantized MoE
+ * expert GEMM at decode and at prefill / training-forward shapes, the weight quantizer
+ * that feeds both, the softmax top-k router, and the per-token log-prob comparison.
+ *
+ * Conventions (all entry points)
+ *   - plain C, no exceptions cross the boundary; the return value is a qarl_status;
+ *     qarl_last_error() gives the text of the last failure on the calling thread;
+ *   - every data pointer is a DEVICE pointer owned by the caller unless the comment says
+ *     "host"; the library never frees or keeps them; descriptor structs live on the host;
+ *   - the library enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and returns without synchronising the host; it allocates nothing;
+ *   - shapes and alignments are checked before any launch; device-side index arrays
+ *     (row_map, expert_offsets, sorted_pairs, target) are trusted to be in range;
+ *   - bf16 tensors are raw 16-bit patterns; e4m3 is the OCP "fn" flavour whose largest
+ *     finite value is 448 (the alpha of the paper's FP quantizer).
+ */
+#ifndef QARL_H
+#define QARL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QARL_OK = 0,
+    QARL_ERR_INVALID_ARG = -1,
+    QARL_ERR_UNSUPPORTED = -2,
+    QARL_ERR_ALIGNMENT = -3,
+    QARL_ERR_WORKSPACE = -4,
+    QARL_ERR_HIP = -5
+} qarl_status;
+
+/* Weight formats (the WxAy schemes of section 2.2). */
+typedef enum {
+    QARL_W4A16_G128 = 1, /* int4 symmetric, one bf16 scale per 128 consecutive k; bf16 activations */
+    QARL_FP8_E4M3_CH = 2 /* e4m3 weights, one fp32 scale per output channel; e4m3 activations, one
+                            fp32 scale per token row */
+} qarl_format;
+
+/* Which kernel family runs the contraction.  Both read the same codes and scales and
+ * form the same dequantized weight s*q; they differ in tiling and accumulation order
+ * (section 3.1: the learner's low-bit forward mirrors the rollout engine's arithmetic
+ * without being bitwise identical). */
+typedef enum { QARL_PATH_AUTO = 0, QARL_PATH_DECODE = 1, QARL_PATH_PREFILL = 2 } qarl_path;
+
+typedef enum {
+    QARL_EPI_NONE = 0,     /* out[i][n] = Y[i][n]                                  (N columns)  */
+    QARL_EPI_SILU_MUL = 1, /* out[i][j] = silu(Y[i][j]) * Y[i][N/2 + j], j < N/2  (N/2 columns) */
+    QARL_EPI_COMBINE = 2   /* out[t][n] = sum_slot combine_w[t][slot] * Y[row of (t,slot)][n]   */
+} qarl_epilogue;
+
+typedef enum { QARL_OUT_BF16 = 0, QARL_OUT_F32 = 1 } qarl_out_dtype;
+
+/* Quantized weights of E matrices [N][K] (K contiguous).  Host struct, device buffers.
+ *   W4A16_G128: codes  uint32 [E][N][K/8]; element 8*j+i of a row sits in bits [4i,4i+3] of
+ *                      word j as q+8, q in [-8,7];
+ *               scales bf16   [E][N][K/128]; dequantized weight = float(scale) * q, exact in
+ *                      fp32 and never rounded to 16 bits.
+ *   FP8_E4M3_CH: codes uint8  [E][N][K] (e4m3 bit patterns); scales float [E][N].
+ * Requirements: K % 128 == 0, N % 16 == 0, buffers 16-byte aligned. */
+typedef struct {
+    int32_t fmt; /* qarl_format */
+    int32_t E, N, K;
+    int32_t group; /* 128 for W4A16_G128, 0 for FP8_E4M3_CH */
+    void *codes;
+    void *scales;
+} qarl_qweight;
+
+const char *qarl_last_error(void);
+
+/* Bytes of `ws` that qarl_qgemm_grouped needs for the given call (0 unless the epilogue is
+ * COMBINE, which stages Y in fp32), and that qarl_token_logprob needs. */
+size_t qarl_qgemm_workspace_bytes(int epilogue, int64_t M, int N);
+size_t qarl_logprob_workspace_bytes(int T, int H, int V);
+
+/* Quant of section 2.2 applied to bf16 master weights w [E][N][K], the on-the-fly
+ * W_lowbit = Quant(theta_BF16) of section 3.1; writes out->codes and out->scales.
+ *   W4A16_G128 (integer Quant, z = 0): per row and group of 128 k, scale =
+ *     bf16_rne(absmax / 7) with an IEEE fp32 divide, q = clamp(rne(w / scale), -8, 7)
+ *     dividing by the stored scale; a zero group gets scale 0 and codes 0.
+ *   FP8_E4M3_CH (FP Quant, alpha = 448): per row, scale = absmax / 448 (fp32),
+ *     code = e4m3_rne_saturating(w / scale); a zero row gets scale 0 and codes +0.
+ * Errors: INVALID_ARG (null pointers, E/N/K <= 0, wrong group), ALIGNMENT, UNSUPPORTED. */
+int qarl_quantize_weights(const void *w_bf16, const qarl_qweight *out, void *stream);
+
+/* FP Quant of section 2.2 with one scale per row, for activations (the s_x of eq. (2)):
+ * x bf16 [rows][K] -> codes uint8 [rows][K], scales float [rows].  K % 8 == 0. */
+int qarl_quantize_rows_fp8(const void *x_bf16, int64_t rows, int K, void *codes, float *scales,
+                           void *stream);
+
+/* MoE router.  Per token: softmax over the E bf16 logits in fp32, the topk experts ordered
+ * by (logit descending, expert id ascending) as slots 0..topk-1, weights = their
+ * probabilities (renormalised to sum 1 if renorm != 0).  Then tokens are grouped by
+ * expert: expert_counts[E], expert_offsets[E+1] (exclusive prefix sum), and the
+ * (token, slot) pairs p = t*topk + slot listed by (expert, t, slot) in sorted_pairs[T*topk];
+ * sorted_tokens[i] = sorted_pairs[i] / topk.  Section 4.1 names the router as where
+ * quantized MoE rollouts drift, so ids and grouping are exact integer work.
+ * Supported: E % 64 == 0, E <= 256, 1 <= topk <= min(E, 32).  T == 0 is a no-op that
+ * still writes zero counts and offsets. */
+int qarl_moe_route(const void *logits_bf16, int T, int E, int topk, int renorm, int32_t *topk_ids,
+                   float *topk_w, int32_t *expert_counts, int32_t *expert_offsets,
+                   int32_t *sorted_pairs, int32_t *sorted_tokens, void *stream);
+
+/* Grouped quantized GEMM, eq. (1) (W4A16: Y = X * (s_w q)^T with 16-bit X) and eq. (2)
+ * (FP8: Y = s_x s_w (X_q W_q^T)), fp32 accumulation.  Row i of the problem, for i in
+ * [expert_offsets[e], expert_offsets[e+1]), multiplies expert e's matrix and reads
+ * activation row row_map[i] (row i if row_map is NULL).  M = expert_offsets[E] must be
+ * passed by the caller (host value).
+ *   x          W4A16: bf16 [x_rows][K];  FP8: uint8 e4m3 [x_rows][K] with x_scales float [x_rows]
+ *   epilogue   NONE:     out [M][N]
+ *              SILU_MUL: rows [0,N/2) of each expert matrix are the gate, [N/2,N) the up
+ *                        projection; out bf16 [M][N/2], rounded once from fp32
+ *              COMBINE:  Y is staged in ws as fp32 [M][N]; out [T][N] sums the topk rows of each
+ *                        token in slot order with weights combine_w [T][topk]; sorted_pairs as
+ *                        written by qarl_moe_route
+ *   out_dtype  QARL_OUT_BF16 or QARL_OUT_F32 (SILU_MUL: bf16 only)
+ *   path       AUTO picks DECODE when the mean rows per expert is small
+ * Errors: INVALID_ARG, ALIGNMENT, UNSUPPORTED (shape outside the kernels' domain),
+ * WORKSPACE (ws too small).  M == 0 is a no-op (COMBINE still zero-fills out). */
+int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scales, int64_t x_rows,
+                       const int32_t *row_map, const int32_t *expert_offsets, int64_t M,
+                       int epilogue, const float *combine_w, const int32_t *sorted_pairs, int T,
+                       int topk, void *out, int out_dtype, int path, void *ws, size_t ws_bytes,
+                       void *stream);
+
+/* LM head fused with the per-token log-prob: z = inv_temperature * h W_lm^T (bf16 inputs,
+ * fp32 accumulation, logits never stored), logprob[t] = z[t][target[t]] - logsumexp_v z[t][v].
+ * If ref_logprob is given, also the mismatch comparison of eq. (3) in log space:
+ * delta[t] = logprob[t] - ref_logprob[t], and per sequence s (tokens
+ * [seq_offsets[s], seq_offsets[s+1])) the sequence-level weight of section 3.2,
+ * seq_w[s] = exp(mean_t delta[t]), with the two-sided cap seq_w_clipped[s] =
+ * exp(clip(mean delta, -log c, log c)), c = tis_cap_c > 1.
+ *   h bf16 [T][H], w_lm bf16 [V][H], target int32 [T]; H % 64 == 0.
+ *   delta, seq_w, seq_w_clipped may each be NULL; seq outputs need seq_offsets and S > 0. */
+int qarl_token_logprob(const void *h_bf16, const void *w_lm_bf16, const int32_t *target, int T,
+                       int H, int V, float inv_temperature, float *logprob,
+                       const float *ref_logprob, const int32_t *seq_offsets, int S,
+                       float tis_cap_c, float *delta, float *seq_w, float *seq_w_clipped, void *ws,
+                       size_t ws_bytes, void *stream);
+
+/* The comparison half of qarl_token_logprob on two existing log-prob streams (learner
+ * and sampler): delta, token weight w = exp(delta) (eq. (3)), seq_w and seq_w_clipped as
+ * above.  Any output may be NULL. */
+int qarl_logprob_mismatch(const float *lp_learner, const float *lp_sampler, int T,
+                          const int32_t *seq_offsets, int S, float tis_cap_c, float *delta,
+                          float *token_w, float *seq_w, float *seq_w_clipped, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QARL_H */

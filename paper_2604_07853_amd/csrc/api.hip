@@ -1,0 +1,305 @@
+// C ABI of the library: argument validation and dispatch only.  See include/qarl.h.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "common.hpp"
+
+namespace qarl {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int check_hip(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return QARL_OK;
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return QARL_ERR_HIP;
+}
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+static int check_qweight(const qarl_qweight *w, const char *who)
+{
+    if (!w) {
+        set_error("%s: null weight descriptor", who);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (w->fmt != QARL_W4A16_G128 && w->fmt != QARL_FP8_E4M3_CH) {
+        set_error("%s: unknown weight format %d", who, w->fmt);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (w->E <= 0 || w->N <= 0 || w->K <= 0) {
+        set_error("%s: E, N, K must be positive (got %d, %d, %d)", who, w->E, w->N, w->K);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (w->K % 128 != 0 || w->N % 16 != 0) {
+        set_error("%s: need K %% 128 == 0 and N %% 16 == 0 (got N=%d, K=%d)", who, w->N, w->K);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (w->fmt == QARL_W4A16_G128 && w->group != 128) {
+        set_error("%s: W4A16 supports group 128 only (got %d)", who, w->group);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (!w->codes || !w->scales) {
+        set_error("%s: null codes or scales buffer", who);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!aligned16(w->codes) || !aligned16(w->scales)) {
+        set_error("%s: codes and scales must be 16-byte aligned", who);
+        return QARL_ERR_ALIGNMENT;
+    }
+    return QARL_OK;
+}
+
+}  // namespace qarl
+
+using namespace qarl;
+
+extern "C" {
+
+const char *qarl_last_error(void) { return g_err; }
+
+size_t qarl_qgemm_workspace_bytes(int epilogue, int64_t M, int N)
+{
+    if (epilogue != QARL_EPI_COMBINE || M <= 0 || N <= 0) return 0;
+    return (size_t)M * (size_t)N * sizeof(float);
+}
+
+size_t qarl_logprob_workspace_bytes(int T, int H, int V)
+{
+    if (T <= 0 || H <= 0 || V <= 0) return 0;
+    return logprob_ws_bytes(T, H, V);
+}
+
+int qarl_quantize_weights(const void *w_bf16, const qarl_qweight *out, void *stream)
+{
+    int rc = check_qweight(out, "qarl_quantize_weights");
+    if (rc) return rc;
+    if (!w_bf16) {
+        set_error("qarl_quantize_weights: null input");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!aligned16(w_bf16)) {
+        set_error("qarl_quantize_weights: input must be 16-byte aligned");
+        return QARL_ERR_ALIGNMENT;
+    }
+    const int64_t rows = (int64_t)out->E * out->N;
+    if (out->fmt == QARL_W4A16_G128)
+        return launch_quantize_int4(w_bf16, rows, out->K, out->codes, out->scales, (hipStream_t)stream);
+    return launch_quantize_fp8_rows(w_bf16, rows, out->K, out->codes, (float *)out->scales, (hipStream_t)stream);
+}
+
+int qarl_quantize_rows_fp8(const void *x_bf16, int64_t rows, int K, void *codes, float *scales, void *stream)
+{
+    if (rows < 0 || K <= 0) {
+        set_error("qarl_quantize_rows_fp8: rows >= 0 and K > 0 required (got %lld, %d)", (long long)rows, K);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (rows == 0) return QARL_OK;
+    if (!x_bf16 || !codes || !scales) {
+        set_error("qarl_quantize_rows_fp8: null pointer");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (K % 8 != 0) {
+        set_error("qarl_quantize_rows_fp8: K %% 8 == 0 required (got %d)", K);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (!aligned16(x_bf16) || ((uintptr_t)codes & 7u)) {
+        set_error("qarl_quantize_rows_fp8: x must be 16-byte and codes 8-byte aligned");
+        return QARL_ERR_ALIGNMENT;
+    }
+    return launch_quantize_fp8_rows(x_bf16, rows, K, codes, scales, (hipStream_t)stream);
+}
+
+int qarl_moe_route(const void *logits_bf16, int T, int E, int topk, int renorm, int32_t *topk_ids, float *topk_w,
+                   int32_t *expert_counts, int32_t *expert_offsets, int32_t *sorted_pairs, int32_t *sorted_tokens,
+                   void *stream)
+{
+    if (T < 0 || E <= 0 || topk <= 0) {
+        set_error("qarl_moe_route: T >= 0, E > 0, topk > 0 required (got %d, %d, %d)", T, E, topk);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (E % 64 != 0 || E > 256 || topk > 32 || topk > E) {
+        set_error("qarl_moe_route: supports E %% 64 == 0, E <= 256, topk <= min(E, 32) (got E=%d, topk=%d)", E, topk);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if ((int64_t)T * topk > 0x7fffffffLL) {
+        set_error("qarl_moe_route: T*topk overflows int32");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (!expert_counts || !expert_offsets || (T > 0 && (!logits_bf16 || !topk_ids || !topk_w || !sorted_pairs || !sorted_tokens))) {
+        set_error("qarl_moe_route: null pointer");
+        return QARL_ERR_INVALID_ARG;
+    }
+    return launch_route(logits_bf16, T, E, topk, renorm, topk_ids, topk_w, expert_counts, expert_offsets,
+                        sorted_pairs, sorted_tokens, (hipStream_t)stream);
+}
+
+int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scales, int64_t x_rows,
+                       const int32_t *row_map, const int32_t *expert_offsets, int64_t M, int epilogue,
+                       const float *combine_w, const int32_t *sorted_pairs, int T, int topk, void *out,
+                       int out_dtype, int path, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_qweight(W, "qarl_qgemm_grouped");
+    if (rc) return rc;
+    if (M < 0 || x_rows < 0) {
+        set_error("qarl_qgemm_grouped: negative M or x_rows");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (epilogue != QARL_EPI_NONE && epilogue != QARL_EPI_SILU_MUL && epilogue != QARL_EPI_COMBINE) {
+        set_error("qarl_qgemm_grouped: unknown epilogue %d", epilogue);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (out_dtype != QARL_OUT_BF16 && out_dtype != QARL_OUT_F32) {
+        set_error("qarl_qgemm_grouped: unknown out_dtype %d", out_dtype);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (path != QARL_PATH_AUTO && path != QARL_PATH_DECODE && path != QARL_PATH_PREFILL) {
+        set_error("qarl_qgemm_grouped: unknown path %d", path);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (epilogue == QARL_EPI_SILU_MUL && (out_dtype != QARL_OUT_BF16 || W->N % 32 != 0)) {
+        set_error("qarl_qgemm_grouped: SILU_MUL needs bf16 output and N %% 32 == 0");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (M > 0x7fffffffLL / 2 || x_rows > 0x7fffffffLL) {
+        set_error("qarl_qgemm_grouped: M or x_rows too large");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (epilogue == QARL_EPI_COMBINE) {
+        if (T < 0 || topk <= 0 || (int64_t)T * topk != M) {
+            set_error("qarl_qgemm_grouped: COMBINE needs T*topk == M (got T=%d, topk=%d, M=%lld)", T, topk, (long long)M);
+            return QARL_ERR_INVALID_ARG;
+        }
+        if (W->N % 4 != 0) {
+            set_error("qarl_qgemm_grouped: COMBINE needs N %% 4 == 0");
+            return QARL_ERR_UNSUPPORTED;
+        }
+    }
+    if (M == 0) return QARL_OK;
+    if (!x || !expert_offsets || !out) {
+        set_error("qarl_qgemm_grouped: null pointer");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (W->fmt == QARL_FP8_E4M3_CH && !x_scales) {
+        set_error("qarl_qgemm_grouped: FP8 needs x_scales");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!aligned16(x) || !aligned16(out)) {
+        set_error("qarl_qgemm_grouped: x and out must be 16-byte aligned");
+        return QARL_ERR_ALIGNMENT;
+    }
+    GemmArgs a;
+    a.fmt = W->fmt;
+    a.E = W->E;
+    a.N = W->N;
+    a.K = W->K;
+    a.codes = W->codes;
+    a.scales = W->scales;
+    a.x = x;
+    a.x_scales = x_scales;
+    a.row_map = row_map;
+    a.out_row_map = nullptr;
+    a.offsets = expert_offsets;
+    a.M = M;
+    a.epilogue = epilogue;
+    a.out = out;
+    a.out_f32 = (out_dtype == QARL_OUT_F32);
+    if (epilogue == QARL_EPI_COMBINE) {
+        if (!combine_w || !sorted_pairs) {
+            set_error("qarl_qgemm_grouped: COMBINE needs combine_w and sorted_pairs");
+            return QARL_ERR_INVALID_ARG;
+        }
+        const size_t need = qarl_qgemm_workspace_bytes(epilogue, M, W->N);
+        if (!ws || ws_bytes < need || !aligned16(ws)) {
+            set_error("qarl_qgemm_grouped: COMBINE needs %zu bytes of 16-byte aligned workspace (got %zu)", need, ws_bytes);
+            return QARL_ERR_WORKSPACE;
+        }
+        a.epilogue = QARL_EPI_NONE;
+        a.out = ws;
+        a.out_f32 = 1;
+        a.out_row_map = sorted_pairs;  // Y lands in pair order: row t*topk + slot
+    }
+    int use = path;
+    if (use == QARL_PATH_AUTO) use = (M <= (int64_t)W->E * 64) ? QARL_PATH_DECODE : QARL_PATH_PREFILL;
+    rc = (use == QARL_PATH_DECODE) ? launch_qgemm_stream(a, st) : launch_qgemm_tile(a, st);
+    if (rc) return rc;
+    if (epilogue == QARL_EPI_COMBINE)
+        return launch_combine((const float *)ws, combine_w, T, topk, W->N, out, out_dtype == QARL_OUT_F32, st);
+    return QARL_OK;
+}
+
+int qarl_logprob_mismatch(const float *lp_learner, const float *lp_sampler, int T, const int32_t *seq_offsets, int S,
+                          float tis_cap_c, float *delta, float *token_w, float *seq_w, float *seq_w_clipped,
+                          void *stream)
+{
+    if (T < 0 || S < 0) {
+        set_error("qarl_logprob_mismatch: negative T or S");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (T == 0 && S == 0) return QARL_OK;
+    if (!lp_learner || !lp_sampler) {
+        set_error("qarl_logprob_mismatch: null log-prob stream");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if ((seq_w || seq_w_clipped) && (!seq_offsets || S <= 0)) {
+        set_error("qarl_logprob_mismatch: sequence outputs need seq_offsets and S > 0");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (seq_w_clipped && !(tis_cap_c > 1.f)) {
+        set_error("qarl_logprob_mismatch: cap c must exceed 1 (got %g)", (double)tis_cap_c);
+        return QARL_ERR_INVALID_ARG;
+    }
+    const bool seq = (seq_w || seq_w_clipped);
+    return launch_mismatch(lp_learner, lp_sampler, T, seq ? seq_offsets : nullptr, seq ? S : 0, tis_cap_c, delta,
+                           token_w, seq_w, seq_w_clipped, (hipStream_t)stream);
+}
+
+int qarl_token_logprob(const void *h_bf16, const void *w_lm_bf16, const int32_t *target, int T, int H, int V,
+                       float inv_temperature, float *logprob, const float *ref_logprob, const int32_t *seq_offsets,
+                       int S, float tis_cap_c, float *delta, float *seq_w, float *seq_w_clipped, void *ws,
+                       size_t ws_bytes, void *stream)
+{
+    if (T < 0 || H <= 0 || V <= 0) {
+        set_error("qarl_token_logprob: T >= 0, H > 0, V > 0 required");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (T == 0) return QARL_OK;
+    if (!h_bf16 || !w_lm_bf16 || !target || !logprob) {
+        set_error("qarl_token_logprob: null pointer");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (H % 64 != 0) {
+        set_error("qarl_token_logprob: H %% 64 == 0 required (got %d)", H);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (!aligned16(h_bf16) || !aligned16(w_lm_bf16)) {
+        set_error("qarl_token_logprob: h and w_lm must be 16-byte aligned");
+        return QARL_ERR_ALIGNMENT;
+    }
+    const size_t need = qarl_logprob_workspace_bytes(T, H, V);
+    if (need && (!ws || ws_bytes < need || !aligned16(ws))) {
+        set_error("qarl_token_logprob: needs %zu bytes of 16-byte aligned workspace (got %zu)", need, ws_bytes);
+        return QARL_ERR_WORKSPACE;
+    }
+    if ((delta || seq_w || seq_w_clipped) && !ref_logprob) {
+        set_error("qarl_token_logprob: comparison outputs need ref_logprob");
+        return QARL_ERR_INVALID_ARG;
+    }
+    int rc = launch_logprob(h_bf16, w_lm_bf16, target, T, H, V, inv_temperature, logprob, ws, (hipStream_t)stream);
+    if (rc) return rc;
+    if (ref_logprob && (delta || seq_w || seq_w_clipped))
+        return qarl_logprob_mismatch(logprob, ref_logprob, T, seq_offsets, S, tis_cap_c, delta, nullptr, seq_w,
+                                     seq_w_clipped, stream);
+    return QARL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Shared device helpers of the QaRL hot-path kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/qarl.h"
+
+namespace qarl {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+constexpr int kWave = 64;
+constexpr int kGroup = 128;  // k per int4 scale group
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// Round-to-nearest-even fp32 -> bf16 bit pattern (NaN kept quiet).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Host-side error plumbing (api.hip).
+void set_error(const char *fmt, ...);
+int check_hip(hipError_t e, const char *what);
+
+// Kernel launchers (one per .hip file); all validate nothing: api.hip does.
+int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *scales, hipStream_t s);
+int launch_quantize_fp8_rows(const void *x, int64_t rows, int K, void *codes, float *scales, hipStream_t s);
+int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w,
+                 int32_t *counts, int32_t *offsets, int32_t *pairs, int32_t *tokens, hipStream_t s);
+
+struct GemmArgs {
+    int fmt;
+    int E, N, K;
+    const void *codes;
+    const void *scales;
+    const void *x;
+    const float *x_scales;
+    const int32_t *row_map;      // gather of activation rows, or null
+    const int32_t *out_row_map;  // scatter of output rows, or null
+    const int32_t *offsets;
+    int64_t M;
+    int epilogue;       // NONE or SILU_MUL here; COMBINE is NONE into ws + combine kernel
+    void *out;          // [M][N] or [M][N/2]
+    int out_f32;
+};
+int launch_qgemm_stream(const GemmArgs &a, hipStream_t s);
+int launch_qgemm_tile(const GemmArgs &a, hipStream_t s);
+int launch_combine(const float *y_pair_order, const float *w, int T, int topk, int N, void *out, int out_f32,
+                   hipStream_t s);
+int launch_logprob(const void *h, const void *wlm, const int32_t *target, int T, int H, int V,
+                   float inv_temp, float *logprob, void *ws, hipStream_t s);
+size_t logprob_ws_bytes(int T, int H, int V);
+int launch_mismatch(const float *lp_a, const float *lp_b, int T, const int32_t *seq_offsets, int S, float c,
+                    float *delta, float *token_w, float *seq_w, float *seq_wc, hipStream_t s);
+
+}  // namespace qarl

@@ -1,0 +1,358 @@
+// Grouped quantized GEMM, MFMA-tiled ("prefill" / training-forward) path: the same
+// contraction as the weight-streaming path (eq. (1) / eq. (2) of section 2.2), on the same
+// codes and scales and with the same exact dequantized weight s*q, for experts that see
+// hundreds to thousands of token rows, where the path is a dense contraction.
+//
+// A workgroup of 8 wavefronts (2 x 4) owns a 128-token x 256-column tile of one expert;
+// each wavefront owns 64 x 64 as 2 x 2 v_mfma_f32_32x32x16 tiles.  Token rows are gathered
+// once per workgroup into a double-buffered LDS tile (one 128-k scale group per step);
+// packed weights go global -> registers and are expanded there, so the LDS only carries the
+// activation operand.  W4A16 group handling is the one described in qgemm_stream.hip: codes
+// become the exact bf16 values (q+24)/16, every scale group accumulates in its own fp32
+// accumulator that starts at -1.5 * sum_k x, and is folded in with one FMA by 16*s.
+#include "common.hpp"
+
+namespace qarl {
+
+constexpr int kTThreads = 512;
+constexpr int kBM = 128;
+constexpr int kBN = 256;
+constexpr int kAStrideB16 = kGroup * 2 + 16;  // bytes per LDS row, bf16 activations
+constexpr int kAStrideF8 = kGroup + 16;       // bytes per LDS row, e4m3 activations
+
+struct TileParams {
+    const uint32_t *codes;
+    const void *scales;
+    const void *x;
+    const float *x_scales;
+    const int32_t *row_map;
+    const int32_t *out_row_map;
+    const int32_t *offsets;
+    void *out;
+    int E, N, K, out_f32;
+    int n_blocks;   // column blocks per expert
+    int m_slots;    // upper bound of 128-row tiles over all experts
+    int total;      // n_blocks * m_slots rounded up to a multiple of 8
+};
+
+__device__ __forceinline__ bf16x8 unpack_int4_word_t(uint32_t w)
+{
+    u32x4 d;
+    d[0] = ((w << 3) & 0x00780078u) | 0x3f803f80u;
+    d[1] = ((w >> 1) & 0x00780078u) | 0x3f803f80u;
+    d[2] = ((w >> 5) & 0x00780078u) | 0x3f803f80u;
+    d[3] = ((w >> 9) & 0x00780078u) | 0x3f803f80u;
+    return __builtin_bit_cast(bf16x8, d);
+}
+
+template <int FMT, int EPI>
+__global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
+    constexpr int kStride = kInt4 ? kAStrideB16 : kAStrideF8;
+    constexpr int kBufBytes = kBM * kStride + kBM * 4;  // tile + per-row group sums
+    __shared__ int s_rows[kBM];
+    __shared__ int s_scan[256];
+    __shared__ int s_expert, s_mtile;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int c = lane & 31, h = lane >> 5;
+
+    // workgroup id -> (m slot, column block): consecutive ids go round-robin over the 8 XCDs, so
+    // give every XCD a contiguous range of tiles: column blocks of one token tile share its L2.
+    const int per_xcd = p.total / 8;
+    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int nb = v % p.n_blocks;
+    const int slot = v / p.n_blocks;
+    if (slot >= p.m_slots) return;
+
+    // slot -> (expert, tile within expert) by a scan over the per-expert tile counts
+    if (tid < 256) {
+        int t = 0;
+        if (tid < p.E) t = (p.offsets[tid + 1] - p.offsets[tid] + kBM - 1) / kBM;
+        s_scan[tid] = t;
+    }
+    if (tid == 0) s_expert = -1;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+        int add = 0;
+        if (tid < 256 && tid >= o) add = s_scan[tid - o];
+        __syncthreads();
+        if (tid < 256) s_scan[tid] += add;
+        __syncthreads();
+    }
+    if (tid < p.E) {
+        const int incl = s_scan[tid];
+        const int excl = tid ? s_scan[tid - 1] : 0;
+        if (slot >= excl && slot < incl) {
+            s_expert = tid;
+            s_mtile = slot - excl;
+        }
+    }
+    __syncthreads();
+    const int e = s_expert;
+    if (e < 0) return;
+    const int row0 = p.offsets[e] + s_mtile * kBM;
+    const int mrem = min(kBM, p.offsets[e + 1] - row0);
+    if (tid < kBM) {
+        const int i = row0 + tid;
+        s_rows[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
+    }
+    __syncthreads();
+
+    const int N = p.N, K = p.K, G = K / kGroup;
+    // weight rows of this lane's two column tiles
+    int nrow[2];
+    if (EPI == QARL_EPI_SILU_MUL) {
+        nrow[0] = nb * (kBN / 2) + wn * 32 + c;
+        nrow[1] = N / 2 + nrow[0];
+    } else {
+        nrow[0] = nb * kBN + wn * 64 + c;
+        nrow[1] = nrow[0] + 32;
+    }
+    bool tile_ok[2];
+    tile_ok[0] = (EPI == QARL_EPI_SILU_MUL) ? (nrow[0] - c + 32 <= N / 2) : (nrow[0] - c + 32 <= N);
+    tile_ok[1] = (EPI == QARL_EPI_SILU_MUL) ? tile_ok[0] : (nrow[1] - c + 32 <= N);
+    const int words_per_row = kInt4 ? K / 8 : K / 4;
+    const uint32_t *wrow[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) wrow[nt] = p.codes + ((int64_t)e * N + (tile_ok[nt] ? nrow[nt] : 0)) * words_per_row;
+
+    // ---- activation tile: 128 rows x 128 k, 16-byte blocks; 16 consecutive lanes cover one row
+    constexpr int kBlkPerRow = kInt4 ? 16 : 8;
+    constexpr int kARegs = kBM * kBlkPerRow / kTThreads;  // 4 or 2
+    u32x4 ar[kARegs];
+    auto load_a = [&](int g) {
+#pragma unroll
+        for (int u = 0; u < kARegs; ++u) {
+            const int idx = u * kTThreads + tid;
+            const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
+            const int xrow = s_rows[r];
+            ar[u] = u32x4{0, 0, 0, 0};
+            if (xrow >= 0) {
+                const unsigned char *src =
+                    (const unsigned char *)p.x + ((int64_t)xrow * K + g * kGroup) * (kInt4 ? 2 : 1) + b * 16;
+                ar[u] = *(const u32x4 *)src;
+            }
+        }
+    };
+    auto store_a = [&](int buf) {
+        unsigned char *xs = smem + buf * kBufBytes;
+        float *sx = (float *)(xs + kBM * kStride);
+#pragma unroll
+        for (int u = 0; u < kARegs; ++u) {
+            const int idx = u * kTThreads + tid;
+            const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
+            u32x4 v4 = ar[u];
+            if (kInt4) {
+                float sum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sum += __uint_as_float(v4[i] << 16) + __uint_as_float(v4[i] & 0xffff0000u);
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
+                if (b == 0) sx[r] = -1.5f * sum;
+                u32x4 o4;  // element order 0,4,1,5,2,6,3,7 inside every 8-block (the unpacked code order)
+                o4[0] = (v4[0] & 0xffffu) | (v4[2] << 16);
+                o4[1] = (v4[0] >> 16) | (v4[2] & 0xffff0000u);
+                o4[2] = (v4[1] & 0xffffu) | (v4[3] << 16);
+                o4[3] = (v4[1] >> 16) | (v4[3] & 0xffff0000u);
+                v4 = o4;
+            }
+            *(u32x4 *)(xs + r * kStride + b * 16) = v4;
+        }
+    };
+
+    // ---- packed weights of one group: lane (c,h) reads k in [128 g + 64 h, +64) of its two rows
+    constexpr int kWRegs = kInt4 ? 2 : 4;  // 16-byte loads per lane and column tile
+    struct BRegs {
+        u32x4 w[2][kWRegs];
+        uint32_t s[2];
+    };
+    auto load_b = [&](BRegs &dst, int g) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+            for (int u = 0; u < kWRegs; ++u) {
+                dst.w[nt][u] = u32x4{0, 0, 0, 0};
+                if (tile_ok[nt]) {
+                    const uint32_t *src = wrow[nt] + (kInt4 ? (g * 16 + h * 8 + u * 4) : (g * 32 + h * 16 + u * 4));
+                    dst.w[nt][u] = *(const u32x4 *)src;
+                }
+            }
+            dst.s[nt] = 0;
+            if (kInt4 && tile_ok[nt]) dst.s[nt] = ((const uint16_t *)p.scales)[((int64_t)e * N + nrow[nt]) * G + g];
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int ms = 0; ms < 2; ++ms)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ms][nt][i] = 0.f;
+
+    BRegs bcur, bnxt;
+    load_a(0);
+    load_b(bcur, 0);
+    store_a(0);
+    __syncthreads();
+    for (int g = 0; g < G; ++g) {
+        if (g + 1 < G) {
+            load_a(g + 1);
+            load_b(bnxt, g + 1);
+        }
+        const unsigned char *xs = smem + (g & 1) * kBufBytes;
+        const float *sx = (const float *)(xs + kBM * kStride);
+        if (kInt4) {
+            f32x16 ag[2][2];
+#pragma unroll
+            for (int ms = 0; ms < 2; ++ms) {
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x4 init = *(const f32x4 *)(sx + wm * 64 + ms * 32 + 8 * i4 + 4 * h);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        ag[ms][0][i4 * 4 + i] = init[i];
+                        ag[ms][1][i4 * 4 + i] = init[i];
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bf16x8 b0 = unpack_int4_word_t(bcur.w[0][j >> 2][j & 3]);
+                const bf16x8 b1 = unpack_int4_word_t(bcur.w[1][j >> 2][j & 3]);
+#pragma unroll
+                for (int ms = 0; ms < 2; ++ms) {
+                    const bf16x8 a =
+                        *(const bf16x8 *)(xs + (wm * 64 + ms * 32 + c) * kStride + (h * 64 + j * 8) * 2);
+                    ag[ms][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, ag[ms][0], 0, 0, 0);
+                    ag[ms][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, ag[ms][1], 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const float s16 = 16.f * bf16_bits_to_f32(bcur.s[nt]);
+#pragma unroll
+                for (int ms = 0; ms < 2; ++ms)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[ms][nt][i] = fmaf(s16, ag[ms][nt][i], acc[ms][nt][i]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const u32x4 w0 = bcur.w[0][j >> 1], w1 = bcur.w[1][j >> 1];
+                const long b0 = (long)(((uint64_t)w0[(j & 1) * 2 + 1] << 32) | w0[(j & 1) * 2]);
+                const long b1 = (long)(((uint64_t)w1[(j & 1) * 2 + 1] << 32) | w1[(j & 1) * 2]);
+#pragma unroll
+                for (int ms = 0; ms < 2; ++ms) {
+                    const long a = *(const long *)(xs + (wm * 64 + ms * 32 + c) * kStride + h * 64 + j * 8);
+                    acc[ms][0] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b0, acc[ms][0], 0, 0, 0);
+                    acc[ms][1] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b1, acc[ms][1], 0, 0, 0);
+                }
+            }
+        }
+        if (g + 1 < G) {
+            store_a((g + 1) & 1);
+            bcur = bnxt;
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane (c,h), register i -> token row 8*(i/4) + 4h + i%4, column c of each tile
+    float swn[2] = {1.f, 1.f};
+    if (!kInt4) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) swn[nt] = tile_ok[nt] ? ((const float *)p.scales)[(int64_t)e * N + nrow[nt]] : 0.f;
+    }
+#pragma unroll
+    for (int ms = 0; ms < 2; ++ms) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int r = wm * 64 + ms * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+            if (r < mrem) {
+                const int64_t srow = (int64_t)row0 + r;
+                const int64_t orow = p.out_row_map ? (int64_t)p.out_row_map[srow] : srow;
+                float v0 = acc[ms][0][i], v1 = acc[ms][1][i];
+                if (!kInt4) {
+                    const float sxr = p.x_scales[s_rows[r]];
+                    v0 *= sxr * swn[0];
+                    v1 *= sxr * swn[1];
+                }
+                if (EPI == QARL_EPI_SILU_MUL) {
+                    if (tile_ok[0]) {
+                        const float a = v0 / (1.f + expf(-v0)) * v1;
+                        ((uint16_t *)p.out)[orow * (N / 2) + nrow[0]] = (uint16_t)f32_to_bf16_bits(a);
+                    }
+                } else if (p.out_f32) {
+                    if (tile_ok[0]) ((float *)p.out)[orow * N + nrow[0]] = v0;
+                    if (tile_ok[1]) ((float *)p.out)[orow * N + nrow[1]] = v1;
+                } else {
+                    if (tile_ok[0]) ((uint16_t *)p.out)[orow * N + nrow[0]] = (uint16_t)f32_to_bf16_bits(v0);
+                    if (tile_ok[1]) ((uint16_t *)p.out)[orow * N + nrow[1]] = (uint16_t)f32_to_bf16_bits(v1);
+                }
+            }
+        }
+    }
+}
+
+template <int FMT, int EPI>
+static int launch_one(const GemmArgs &a, hipStream_t s)
+{
+    constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
+    if (a.E > 256) {
+        set_error("qgemm (prefill path): at most 256 experts (got %d)", a.E);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (a.N % 32 != 0) {
+        set_error("qgemm (prefill path): N %% 32 == 0 required (got %d)", a.N);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    TileParams p;
+    p.codes = (const uint32_t *)a.codes;
+    p.scales = a.scales;
+    p.x = a.x;
+    p.x_scales = a.x_scales;
+    p.row_map = a.row_map;
+    p.out_row_map = a.out_row_map;
+    p.offsets = a.offsets;
+    p.out = a.out;
+    p.E = a.E;
+    p.N = a.N;
+    p.K = a.K;
+    p.out_f32 = a.out_f32;
+    p.n_blocks = (EPI == QARL_EPI_SILU_MUL) ? (a.N / 2 + kBN / 2 - 1) / (kBN / 2) : (a.N + kBN - 1) / kBN;
+    const int64_t slots = (a.M + kBM - 1) / kBM + a.E;
+    const int64_t total = ((slots * p.n_blocks + 7) / 8) * 8;
+    if (total > 0x7fffffffLL) {
+        set_error("qgemm (prefill path): grid too large");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    p.m_slots = (int)slots;
+    p.total = (int)total;
+    const int stride = kInt4 ? kAStrideB16 : kAStrideF8;
+    const size_t lds = 2 * ((size_t)kBM * stride + kBM * 4);
+    static bool attr_done = false;
+    auto kern = qgemm_tile_kernel<FMT, EPI>;
+    if (!attr_done) {
+        int rc = check_hip(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
+                           "hipFuncSetAttribute(tile)");
+        if (rc) return rc;
+        attr_done = true;
+    }
+    kern<<<dim3((unsigned)total), dim3(kTThreads), lds, s>>>(p);
+    return check_hip(hipGetLastError(), "qgemm_tile_kernel");
+}
+
+int launch_qgemm_tile(const GemmArgs &a, hipStream_t s)
+{
+    if (a.fmt == QARL_W4A16_G128)
+        return a.epilogue == QARL_EPI_SILU_MUL ? launch_one<QARL_W4A16_G128, QARL_EPI_SILU_MUL>(a, s)
+                                               : launch_one<QARL_W4A16_G128, QARL_EPI_NONE>(a, s);
+    return a.epilogue == QARL_EPI_SILU_MUL ? launch_one<QARL_FP8_E4M3_CH, QARL_EPI_SILU_MUL>(a, s)
+                                           : launch_one<QARL_FP8_E4M3_CH, QARL_EPI_NONE>(a, s);
+}
+
+}  // namespace qarl

@@ -1,0 +1,183 @@
+// MoE router: fp32 softmax over bf16 logits, exact top-k by (logit desc, expert id asc),
+// renormalised weights, then a stable grouping of the (token, slot) pairs by expert.
+// One wavefront owns one token: E <= 256 logits sit 1..4 per lane, the arg-max of every
+// round is a 6-step shuffle reduction on an integer key, so equal bf16 logits resolve to
+// the lower expert id exactly as a full stable sort would.
+#include "common.hpp"
+
+namespace qarl {
+
+constexpr int kRouteThreads = 256;
+constexpr int kMaxPerLane = 4;  // E <= 256
+
+// Order-preserving integer image of a bf16 pattern (-0 counted as +0), high half of the key;
+// low half = 0xffff - expert id so that the lower id wins among equal logits.
+__device__ __forceinline__ uint32_t sort_key(uint32_t h, int id)
+{
+    if (h == 0x8000u) h = 0;
+    uint32_t k = (h & 0x8000u) ? (~h & 0xffffu) : (h | 0x8000u);
+    return (k << 16) | (0xffffu - (uint32_t)id);
+}
+
+__global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(const uint16_t *__restrict__ logits, int T,
+                                                                  int E, int topk, int renorm,
+                                                                  int32_t *__restrict__ ids,
+                                                                  float *__restrict__ wts,
+                                                                  int32_t *__restrict__ counts)
+{
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * (kRouteThreads / 64) + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const int per = E / 64;
+    uint32_t key[kMaxPerLane];
+    float val[kMaxPerLane];
+#pragma unroll
+    for (int j = 0; j < kMaxPerLane; ++j) {
+        key[j] = 0;
+        val[j] = -INFINITY;
+        if (j < per) {
+            const int e = lane + 64 * j;
+            const uint32_t h = logits[(int64_t)t * E + e];
+            key[j] = sort_key(h, e);
+            val[j] = bf16_bits_to_f32(h);
+        }
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < kMaxPerLane; ++j) m = fmaxf(m, val[j]);
+    m = wave_max(m);
+    float z = 0.f;
+#pragma unroll
+    for (int j = 0; j < kMaxPerLane; ++j)
+        if (j < per) z += expf(val[j] - m);
+    z = wave_sum(z);
+
+    int my_id = 0;      // lane r keeps the r-th winner
+    float my_p = 0.f;
+    float psum = 0.f;
+    for (int r = 0; r < topk; ++r) {
+        uint32_t best = 0;
+#pragma unroll
+        for (int j = 0; j < kMaxPerLane; ++j) best = max(best, key[j]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) best = max(best, (uint32_t)__shfl_xor((int)best, o, 64));
+        const int e = 0xffff - (int)(best & 0xffffu);
+        // the owner retires the winner and publishes its logit
+        float lv = 0.f;
+#pragma unroll
+        for (int j = 0; j < kMaxPerLane; ++j)
+            if (key[j] == best) {
+                lv = val[j];
+                key[j] = 0;
+            }
+        lv = __shfl(lv, e & 63, 64);
+        const float p = expf(lv - m) / z;
+        psum += p;
+        if (lane == r) {
+            my_id = e;
+            my_p = p;
+        }
+    }
+    if (lane < topk) {
+        ids[(int64_t)t * topk + lane] = my_id;
+        wts[(int64_t)t * topk + lane] = renorm ? my_p / psum : my_p;
+        atomicAdd(&counts[my_id], 1);
+    }
+}
+
+__global__ void zero_i32_kernel(int32_t *p, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// One workgroup per expert: its offset is the sum of the counts before it; it then walks all
+// pairs in ascending order and compacts the ones routed to it, which keeps (t, slot) order.
+constexpr int kGroupThreads = 256;
+constexpr int kPairsPerThread = 4;
+
+__global__ __launch_bounds__(kGroupThreads) void group_by_expert_kernel(const int32_t *__restrict__ ids,
+                                                                       int n_pairs, int E, int topk,
+                                                                       const int32_t *__restrict__ counts,
+                                                                       int32_t *__restrict__ offsets,
+                                                                       int32_t *__restrict__ pairs,
+                                                                       int32_t *__restrict__ tokens)
+{
+    __shared__ int s_wave[kGroupThreads / 64];
+    __shared__ int s_base;
+    const int e = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // exclusive offset of this expert
+    int part = 0;
+    for (int i = threadIdx.x; i < e; i += kGroupThreads) part += counts[i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+    if (lane == 0) s_wave[wave] = part;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int b = 0;
+        for (int i = 0; i < kGroupThreads / 64; ++i) b += s_wave[i];
+        s_base = b;
+        offsets[e] = b;
+        if (e == E - 1) offsets[E] = b + counts[e];
+    }
+    __syncthreads();
+    int running = s_base;
+    const int chunk = kGroupThreads * kPairsPerThread;
+    for (int p0 = 0; p0 < n_pairs; p0 += chunk) {
+        const int p = p0 + threadIdx.x * kPairsPerThread;
+        int hit[kPairsPerThread];
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < kPairsPerThread; ++j) {
+            hit[j] = (p + j < n_pairs) && (ids[p + j] == e);
+            cnt += hit[j];
+        }
+        // exclusive scan of cnt over the workgroup
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            int v = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += v;
+        }
+        __syncthreads();  // previous iteration's readers of s_wave are done
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int i = 0; i < kGroupThreads / 64; ++i) {
+            int v = s_wave[i];
+            if (i < wave) before += v;
+            total += v;
+        }
+        int pos = running + before + incl - cnt;
+#pragma unroll
+        for (int j = 0; j < kPairsPerThread; ++j)
+            if (hit[j]) {
+                pairs[pos] = p + j;
+                tokens[pos] = (p + j) / topk;
+                ++pos;
+            }
+        running += total;
+    }
+}
+
+int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w,
+                 int32_t *counts, int32_t *offsets, int32_t *pairs, int32_t *tokens, hipStream_t s)
+{
+    zero_i32_kernel<<<dim3((E + 255) / 256), dim3(256), 0, s>>>(counts, E);
+    int rc = check_hip(hipGetLastError(), "zero_i32_kernel");
+    if (rc) return rc;
+    if (T > 0) {
+        const int per_block = kRouteThreads / 64;
+        route_topk_kernel<<<dim3((T + per_block - 1) / per_block), dim3(kRouteThreads), 0, s>>>(
+            (const uint16_t *)logits, T, E, topk, renorm, ids, w, counts);
+        rc = check_hip(hipGetLastError(), "route_topk_kernel");
+        if (rc) return rc;
+    }
+    group_by_expert_kernel<<<dim3(E), dim3(kGroupThreads), 0, s>>>(ids, T * topk, E, topk, counts, offsets,
+                                                                   pairs, tokens);
+    return check_hip(hipGetLastError(), "group_by_expert_kernel");
+}
+
+}  // namespace qarl

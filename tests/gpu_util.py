@@ -1,0 +1,62 @@
+"""Helpers shared by the GPU parity tests."""
+import numpy as np
+import torch
+
+from paper_2604_07853_amd import synth
+
+
+def dev(t):
+    return t.cuda()
+
+
+def np_bits(t):
+    return synth.bits(t)
+
+
+def to_np(t):
+    t = t.detach().cpu()
+    if t.dtype == torch.bfloat16:
+        return t.double().numpy()
+    return t.numpy()
+
+
+def norm_err(got, ref):
+    """max |got - ref| / (|ref| + rms(ref)): relative error that stays meaningful near zero."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = np.sqrt((ref ** 2).mean()) if ref.size else 0.0
+    if ref.size == 0:
+        return 0.0
+    return float((np.abs(got - ref) / (np.abs(ref) + rms + 1e-300)).max())
+
+
+def bf16_half_ulp(ref):
+    """Half the spacing of bf16 (8 significant bits) at |ref|: the output format's own rounding."""
+    a = np.abs(np.asarray(ref, dtype=np.float64))
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -126)))
+    return 2.0 ** (e - 8)
+
+
+def norm_err_bf16(got, ref):
+    """norm_err of a bf16 output after discounting the final rounding to bf16 itself, which any
+    bf16 result (the oracle's too) carries: max (|got - ref| - half_ulp(ref))+ / (|ref| + rms)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = np.sqrt((ref ** 2).mean())
+    d = np.maximum(np.abs(got - ref) - bf16_half_ulp(ref) * (1 + 1e-9), 0.0)
+    return float((d / (np.abs(ref) + rms + 1e-300)).max())
+
+
+def flip_fraction(got_bits, ref_bits):
+    """Fraction of bf16 outputs whose bit pattern differs from the oracle's rounded output."""
+    return float((np.asarray(got_bits) != np.asarray(ref_bits)).mean())
+
+
+def bf16_ulp_diff(a_bits, b_bits):
+    """Distance in bf16 ulps between two bit-pattern arrays (sign-magnitude aware)."""
+    def key(x):
+        x = x.astype(np.int32)
+        return np.where(x & 0x8000, -(x & 0x7fff), x & 0x7fff)
+    return np.abs(key(np.asarray(a_bits)) - key(np.asarray(b_bits)))
