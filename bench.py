@@ -1,0 +1,291 @@
+"""Benchmark of the QaRL low-bit MoE hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras] [--no-cpu]
+
+A step is one pass of the decode-shaped W4A16 MoE layer (route -> group -> gate_up GEMM with
+SiLU*mul -> down GEMM -> weighted combine) over one batch of 256 synthetic tokens with
+Qwen3-30B-A3B expert shapes (128 experts, hidden 2048, intermediate 768, top-8), every input
+already resident in HBM.  The quantized weights rotate over several distinct copies so that the
+256 MB last-level cache cannot serve a 311 MB layer twice.  Prints ONE JSON line: the decode
+figure as `value` (algorithmic GB/s), the roofline of the dominant kernel, the oracle timed on
+the host cores, and under `extra` the other rows of the path (prefill TFLOP/s, quantize GB/s,
+FP8, LM-head log-prob, the 48-layer sweep).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TF = 2500.0
+MFMA_FP8_PEAK_TF = 5000.0
+
+
+def weight_bytes_w4a16(E, N, K):
+    return E * N * (K // 2 + K // 128 * 2)
+
+
+def weight_bytes_fp8(E, N, K):
+    return E * N * (K + 4)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--copies", type=int, default=4, help="distinct weight copies the steps rotate over")
+    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--sweep-layers", type=int, default=48)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not "
+                 "supported, run with --gpus 1" % args.gpus)
+
+    import numpy as np
+    import torch
+    from paper_2604_07853_amd import binding as q
+    from paper_2604_07853_amd import synth
+
+    q.lib()
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    E, H, I, TOPK = synth.E, synth.H, synth.I, synth.TOPK
+    T = 256
+    M = T * TOPK
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, iters, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters  # ms
+
+    # ---- weights: `copies` independently drawn layers, quantized by the library's own kernel
+    layers = []
+    masters0 = None
+    for c in range(args.copies):
+        gu, dn = synth.expert_weights(E, H, I, seed=1000 + 2 * c, device=dev)
+        qgu = q.qarl_quantize_weights(gu)
+        qdn = q.qarl_quantize_weights(dn)
+        if c == 0:
+            masters0 = (gu, dn)
+        else:
+            del gu, dn
+        layers.append(q.MoELayer(qgu, qdn, T, TOPK, q.QARL_PATH_DECODE, dev))
+    xs = [synth.normal_bf16((T, H), 1.0, seed=10 + i, device=dev) for i in range(4)]
+    lgs = [synth.router_logits(T, E, seed=20 + i, device=dev) for i in range(4)]
+    torch.cuda.synchronize()
+
+    state = {"i": 0}
+    gu_events = []
+
+    def step(record=False):
+        i = state["i"]
+        state["i"] += 1
+        layer = layers[i % len(layers)]
+        x, lg = xs[i % 4], lgs[i % 4]
+        r = q.qarl_moe_route(lg, TOPK, True, out=layer.routing)
+        if record:
+            a, b = ev(), ev()
+            a.record()
+        q.qarl_qgemm_grouped(layer.gu, x, r.offsets, M, row_map=r.tokens, epilogue=q.QARL_EPI_SILU_MUL,
+                             out=layer.a, path=q.QARL_PATH_DECODE)
+        if record:
+            b.record()
+            gu_events.append((a, b))
+        q.qarl_qgemm_grouped(layer.dn, layer.a, r.offsets, M, epilogue=q.QARL_EPI_COMBINE, combine_w=r.w,
+                             sorted_pairs=r.pairs, T=T, topk=TOPK, out=layer.out, path=q.QARL_PATH_DECODE,
+                             ws=layer.ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0, t1 = ev(), ev()
+    t0.record()
+    for _ in range(args.steps):
+        step(record=True)
+    t1.record()
+    torch.cuda.synchronize()
+    ms_step = t0.elapsed_time(t1) / args.steps
+    ms_gu = float(np.mean([a.elapsed_time(b) for a, b in gu_events]))
+
+    # algorithmic bytes of a step: every expert's codes + scales once, logits, x, a (written + read), out
+    counts = layers[0].routing.counts.cpu().numpy()
+    active = int((counts > 0).sum())
+    w_gu = weight_bytes_w4a16(E, 2 * I, H) * active // E
+    w_dn = weight_bytes_w4a16(E, H, I) * active // E
+    act = T * E * 2 + T * H * 2 + 2 * M * I * 2 + T * H * 2
+    step_bytes = w_gu + w_dn + act
+    gu_bytes = w_gu + T * H * 2 + M * I * 2
+    value = step_bytes / (ms_step * 1e-3) / 1e9
+    gu_gbs = gu_bytes / (ms_gu * 1e-3) / 1e9
+
+    result = {
+        "metric": "MoE quant GEMM: decode HBM GB/s + prefill TFLOP/s, % of MI355X roofline",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int4 weights x bf16 activations, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "moe_decode_w4a16: 256 tokens, 128 experts x (gate_up [1536,2048] + down [2048,768]) "
+                               "int4 g128, top-8, bf16 out", "tokens": T, "experts": E, "active_experts": active,
+                   "weight_copies": args.copies, "step_bytes": step_bytes, "step_flop": synth.flops_moe(T)},
+        "roofline": {"bound": "hbm", "kernel": "qgemm_stream_kernel<W4A16, SILU_MUL> (gate_up)",
+                     "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "bytes_per_launch": gu_bytes, "ms_per_launch": round(ms_gu, 5),
+                     "step_frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
+    }
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload
+    if not args.no_cpu:
+        import oracle
+        gu, dn = masters0
+        n_steps_cpu = 4
+        guc, gus = oracle.quantize_int4(synth.bits(gu))
+        dnc, dns = oracle.quantize_int4(synth.bits(dn))
+        xb = [synth.bits(x) for x in xs[:n_steps_cpu]]
+        lb = [synth.bits(l) for l in lgs[:n_steps_cpu]]
+        c0 = time.perf_counter()
+        for i in range(n_steps_cpu):
+            oracle.moe_ffn_w4a16(xb[i], lb[i], guc, gus, dnc, dns, TOPK)
+        cpu_s = (time.perf_counter() - c0) / n_steps_cpu
+        result["cpu_baseline"] = {"value": round(step_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": oracle.cores(),
+                                  "kind": "oracle", "sample": "%d full steps of the same layer (256 tokens, all 128 "
+                                  "experts), %.2f s per step" % (n_steps_cpu, cpu_s)}
+    del masters0
+
+    # ---- the other rows of the path, each timed on its own
+    if not args.no_extras:
+        extra = {}
+        # (a1) int4 re-quantization of one layer's masters
+        gu, dn = synth.expert_weights(E, H, I, seed=5000, device=dev)
+        outq = q.QWeight.empty(q.QARL_W4A16_G128, E, 2 * I, H, dev)
+        ms = timed(lambda: q.qarl_quantize_weights(gu, out=outq), 20, 3)
+        qb = gu.numel() * 2 + weight_bytes_w4a16(E, 2 * I, H)
+        extra["quantize_int4_gate_up"] = {"ms": round(ms, 4), "GB/s": round(qb / ms / 1e6, 1),
+                                          "frac_hbm": round(qb / ms / 1e6 / HBM_PEAK_GBS, 4), "bytes": qb}
+        outf = q.QWeight.empty(q.QARL_FP8_E4M3_CH, E, 2 * I, H, dev)
+        ms = timed(lambda: q.qarl_quantize_weights(gu, q.QARL_FP8_E4M3_CH, out=outf), 20, 3)
+        qb8 = gu.numel() * 2 + weight_bytes_fp8(E, 2 * I, H)
+        extra["quantize_fp8_gate_up"] = {"ms": round(ms, 4), "GB/s": round(qb8 / ms / 1e6, 1),
+                                         "frac_hbm": round(qb8 / ms / 1e6 / HBM_PEAK_GBS, 4), "bytes": qb8}
+        qdn8 = q.qarl_quantize_weights(dn, q.QARL_FP8_E4M3_CH)
+        del gu, dn
+
+        # (a6-a9) prefill / training-forward shape, W4A16: 8 x 2048 tokens, Zipf-skewed router
+        Tp = 16384
+        xp = synth.normal_bf16((Tp, H), 1.0, seed=30, device=dev)
+        lgp = synth.router_logits(Tp, E, seed=31, device=dev, zipf_s=1.1)
+        lp_layer = q.MoELayer(layers[0].gu, layers[0].dn, Tp, TOPK, q.QARL_PATH_PREFILL, dev)
+        ms_all = timed(lambda: lp_layer.forward(xp, lgp), 10, 2)
+        r = lp_layer.routing
+        Mp = Tp * TOPK
+        ms_gu_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.gu, xp, r.offsets, Mp, row_map=r.tokens,
+                                                     epilogue=q.QARL_EPI_SILU_MUL, out=lp_layer.a,
+                                                     path=q.QARL_PATH_PREFILL), 10, 2)
+        ms_dn_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.dn, lp_layer.a, r.offsets, Mp, out=lp_layer.ws.view(torch.float32)[:Mp * H].view(Mp, H),
+                                                     out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_PREFILL), 10, 2)
+        fl_gu, fl_dn = 2 * Mp * 2 * I * H, 2 * Mp * H * I
+        extra["prefill_w4a16_16384tok_zipf"] = {
+            "layer_ms": round(ms_all, 4), "gate_up_ms": round(ms_gu_p, 4), "down_ms": round(ms_dn_p, 4),
+            "gemm_TFLOP/s": round((fl_gu + fl_dn) / (ms_gu_p + ms_dn_p) / 1e9, 1),
+            "gemm_frac_mfma_bf16": round((fl_gu + fl_dn) / (ms_gu_p + ms_dn_p) / 1e9 / MFMA_BF16_PEAK_TF, 4),
+            "layer_TFLOP/s": round((fl_gu + fl_dn) / ms_all / 1e9, 1),
+            "max_expert_rows": int(r.counts.max()), "min_expert_rows": int(r.counts.min())}
+        lgu = synth.router_logits(Tp, E, seed=32, device=dev)
+        ms_all_u = timed(lambda: lp_layer.forward(xp, lgu), 10, 2)
+        extra["prefill_w4a16_16384tok_uniform"] = {"layer_ms": round(ms_all_u, 4),
+                                                   "layer_TFLOP/s": round((fl_gu + fl_dn) / ms_all_u / 1e9, 1)}
+
+        # (a10, a11) LM head + log-prob on the layer's output
+        V = synth.V
+        wlm = synth.normal_bf16((V, H), 0.02, seed=40, device=dev)
+        tg = synth.targets(Tp, V, seed=41, device=dev)
+        ws = torch.empty((q.qarl_logprob_workspace_bytes(Tp, H, V),), dtype=torch.uint8, device=dev)
+        hh = lp_layer.out
+        ms_lp = timed(lambda: q.qarl_token_logprob(hh, wlm, tg, ws=ws), 3, 1)
+        fl_lp = 2 * Tp * H * V
+        extra["lm_head_logprob_16384x151936"] = {"ms": round(ms_lp, 3), "TFLOP/s": round(fl_lp / ms_lp / 1e9, 1),
+                                                 "frac_mfma_bf16": round(fl_lp / ms_lp / 1e9 / MFMA_BF16_PEAK_TF, 4)}
+        del wlm, ws, lp_layer, xp
+
+        # FP8 W8A8 layer at 256 and 8192 tokens
+        qgu8 = outf
+        for T8, path, tag in ((256, q.QARL_PATH_DECODE, "decode"), (8192, q.QARL_PATH_PREFILL, "prefill")):
+            x8 = synth.normal_bf16((T8, H), 1.0, seed=50, device=dev)
+            lg8 = synth.router_logits(T8, E, seed=51, device=dev)
+            l8 = q.MoELayer(qgu8, qdn8, T8, TOPK, path, dev)
+            ms8 = timed(lambda: l8.forward(x8, lg8), 20, 3)
+            b8 = weight_bytes_fp8(E, 2 * I, H) + weight_bytes_fp8(E, H, I)
+            f8 = synth.flops_moe(T8)
+            extra["fp8_%s_%dtok" % (tag, T8)] = {"layer_ms": round(ms8, 4), "weight_GB/s": round(b8 / ms8 / 1e6, 1),
+                                                 "frac_hbm": round(b8 / ms8 / 1e6 / HBM_PEAK_GBS, 4),
+                                                 "TFLOP/s": round(f8 / ms8 / 1e9, 1),
+                                                 "frac_mfma_fp8": round(f8 / ms8 / 1e9 / MFMA_FP8_PEAK_TF, 4)}
+            del l8
+        del qgu8, qdn8, outf, outq
+
+        # 48-layer stack: re-quantize every layer after a simulated update, then decode at 512 tokens
+        L = args.sweep_layers
+        if L > 0:
+            T5 = 512
+            masters, quant = [], []
+            for l in range(L):
+                gu, dn = synth.expert_weights(E, H, I, seed=7000 + 2 * l, device=dev)
+                masters.append((gu, dn))
+                quant.append((q.QWeight.empty(q.QARL_W4A16_G128, E, 2 * I, H, dev),
+                              q.QWeight.empty(q.QARL_W4A16_G128, E, H, I, dev)))
+            for l in range(L):   # the simulated update: w += N(0, 1e-4), rounded to bf16
+                masters[l] = (synth.perturb(masters[l][0], 1e-4, 8000 + l), synth.perturb(masters[l][1], 1e-4, 9000 + l))
+
+            def requant():
+                for l in range(L):
+                    q.qarl_quantize_weights(masters[l][0], out=quant[l][0])
+                    q.qarl_quantize_weights(masters[l][1], out=quant[l][1])
+            ms_rq = timed(requant, 3, 1)
+            rq_bytes = L * (E * 3 * I * H * 2 + weight_bytes_w4a16(E, 2 * I, H) + weight_bytes_w4a16(E, H, I))
+            del masters
+            lay5 = [q.MoELayer(quant[l][0], quant[l][1], T5, TOPK, q.QARL_PATH_DECODE, dev) for l in range(L)]
+            x5 = [synth.normal_bf16((T5, H), 1.0, seed=60 + l, device=dev) for l in range(4)]
+            lg5 = [synth.router_logits(T5, E, seed=70 + l, device=dev) for l in range(4)]
+
+            def sweep():
+                for l in range(L):
+                    lay5[l].forward(x5[l % 4], lg5[l % 4])
+            ms_sw = timed(sweep, 5, 1)
+            sw_bytes = L * (weight_bytes_w4a16(E, 2 * I, H) + weight_bytes_w4a16(E, H, I))
+            extra["stack_requantize_%dlayers" % L] = {"ms": round(ms_rq, 3), "GB/s": round(rq_bytes / ms_rq / 1e6, 1),
+                                                      "frac_hbm": round(rq_bytes / ms_rq / 1e6 / HBM_PEAK_GBS, 4)}
+            extra["stack_decode_sweep_%dlayers_512tok" % L] = {
+                "ms": round(ms_sw, 3), "weight_GB/s": round(sw_bytes / ms_sw / 1e6, 1),
+                "frac_hbm": round(sw_bytes / ms_sw / 1e6 / HBM_PEAK_GBS, 4),
+                "TFLOP/s": round(L * synth.flops_moe(T5) / ms_sw / 1e9, 1)}
+        result["extra"] = extra
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

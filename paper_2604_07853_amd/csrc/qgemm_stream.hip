@@ -1,12 +1,15 @@
 // Grouped quantized GEMM, weight-streaming ("decode") path: eq. (1) / eq. (2) of
 // section 2.2 when every expert sees only a few token rows, so the kernel is bound by
-// reading each expert's packed weights from HBM exactly once.
+// reading each expert's packed weights from HBM exactly once (the regime the paper's
+// appendix on quantization schemes calls memory-bound).
 //
-// Layout of the work: a workgroup of 4 wavefronts owns (expert, block of weight rows);
-// each wavefront owns two 16-row weight tiles for the whole K and up to 64 token rows.
-// Packed codes go global -> registers (one 16-byte load per lane and scale group, 64
-// contiguous bytes per weight row), are expanded in registers to bf16 MFMA operands, and
-// meet the token rows, staged once per workgroup in LDS, in v_mfma_f32_16x16x32.
+// Work layout.  A workgroup of 8 wavefronts owns (expert, slice of its weight rows, block
+// of <= 16*MT token rows).  It gathers its token rows ONCE into LDS for the whole K; after
+// that single barrier every wavefront runs on its own: it walks its pairs of 16-row weight
+// tiles and, per pair, the K/128 scale groups, with the packed codes of the next R groups
+// always in flight in a register ring (global -> registers, one 16-byte load per lane,
+// tile and group).  Codes are expanded in registers to bf16 MFMA operands and meet the
+// token rows from LDS in v_mfma_f32_16x16x32.
 //
 // W4A16 numerics: the dequantized weight is s*q exactly.  The nibble u = q+8 is placed in
 // the top mantissa bits of bf16 1.0, giving the exact bf16 value (q+24)/16 with one shift
@@ -14,19 +17,18 @@
 // accumulator, started at -1.5 * sum_k x (which cancels the +24/16 offset), and is folded
 // into the running sum with one fp32 FMA by 16*s.  A one-hot activation row therefore
 // reproduces s*q bit for bit.
+//
+// Experts with more than 16*MT rows: the grid carries m_split row blocks per (expert,
+// slice), mapped to consecutive workgroups of the same XCD so that their identical weight
+// reads meet in that XCD's L2; rows beyond 16*MT*m_split take further passes.
 #include <math.h>
 
 #include "common.hpp"
 
 namespace qarl {
 
-constexpr int kSThreads = 256;
-constexpr int kSWaves = 4;
-constexpr int kMT = 4;                 // 16-row token tiles per pass (64 rows)
-constexpr int kRows = kMT * 16;
-constexpr int kMaxGC = 4;              // scale groups (128 k) per staged chunk, at most
-// LDS row stride in bytes: the chunk's k plus 16 bytes, so consecutive rows skew by 4 banks
-__host__ __device__ constexpr int x_stride(bool int4, int gc) { return gc * kGroup * (int4 ? 2 : 1) + 16; }
+constexpr int kSThreads = 512;
+constexpr int kSWaves = 8;
 
 struct StreamParams {
     const uint32_t *codes;   // int4: [E][N][K/8] words; fp8: bytes viewed as words [E][N][K/4]
@@ -37,7 +39,10 @@ struct StreamParams {
     const int32_t *out_row_map;
     const int32_t *offsets;
     void *out;
-    int N, K, out_f32, n_units;  // n_units: wave work items per expert (tile pairs)
+    int E, N, K, out_f32;
+    int n_units;     // pairs of 16-row weight tiles per expert
+    int n_slices;    // workgroups along the weight rows of one expert
+    int m_split;     // row blocks per (expert, slice) in the grid
 };
 
 __device__ __forceinline__ bf16x8 unpack_int4_word(uint32_t w)
@@ -51,273 +56,290 @@ __device__ __forceinline__ bf16x8 unpack_int4_word(uint32_t w)
     return __builtin_bit_cast(bf16x8, d);
 }
 
-template <int GC, int WH>
-struct WRegs {
-    u32x4 w[2][GC][WH];  // [tile][group in chunk][16-byte part]
-    uint32_t s[2][GC];   // int4: bf16 scale bits
-};
+// LDS bytes per activation row: the row plus 16 bytes, so consecutive rows skew by 4 banks.
+__host__ __device__ constexpr int x_stride(bool int4, int K) { return K * (int4 ? 2 : 1) + 16; }
 
-// One pass over the whole K for up to MTC*16 token rows of expert e, GC scale groups per chunk.
-template <int FMT, int EPI, int MTC, int GC>
-__device__ __forceinline__ void stream_pass(const StreamParams &p, unsigned char *smem, int e, int row0, int m0,
-                                            int mrem, const int (&nrow)[2], const bool (&tile_ok)[2],
-                                            const uint32_t *const (&wrow)[2])
-{
-    constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
-    constexpr int kKC = GC * kGroup;
-    constexpr int kStride = x_stride(kInt4, GC);
-    constexpr int kWH = kInt4 ? 1 : 2;
-    int *s_row = (int *)smem;                                       // [kRows] activation row ids
-    float *sx = (float *)(smem + kRows * 4);                        // int4: [GC][kRows]  -1.5 * group sums
-    unsigned char *xs = smem + kRows * 4 + kMaxGC * kRows * 4;      // [MTC*16][kStride]
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int c = lane & 15, q = lane >> 4;
-    const int N = p.N, K = p.K;
-    const int G = K / kGroup;
-    const int n_chunks = (K + kKC - 1) / kKC;
-
-    __syncthreads();
-    if (tid < kRows) {
-        int i = row0 + m0 + tid;
-        s_row[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
-    }
-    __syncthreads();
-
-    f32x4 acc[2][MTC];
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < MTC; ++mt) acc[nt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // activation chunk: 16-byte blocks, row-major, prefetched into registers
-    constexpr int kBlkPerRow = kInt4 ? kKC / 8 : kKC / 16;        // 64 or 32
-    constexpr int kXRegs = MTC * 16 * kBlkPerRow / kSThreads;     // 4*MTC or 2*MTC
-    u32x4 xr[kXRegs];
-    auto load_x = [&](int kc) {
-        const int nblk = min(kBlkPerRow, (K - kc * kKC) / (kInt4 ? 8 : 16));
-#pragma unroll
-        for (int u = 0; u < kXRegs; ++u) {
-            const int idx = u * kSThreads + tid;
-            const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
-            const int xrow = s_row[r];
-            xr[u] = u32x4{0, 0, 0, 0};
-            if (xrow >= 0 && b < nblk) {
-                const unsigned char *src =
-                    (const unsigned char *)p.x + ((int64_t)xrow * K + kc * kKC) * (kInt4 ? 2 : 1) + b * 16;
-                xr[u] = *(const u32x4 *)src;
-            }
-        }
-    };
-    auto store_x = [&]() {
-#pragma unroll
-        for (int u = 0; u < kXRegs; ++u) {
-            const int idx = u * kSThreads + tid;
-            const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
-            u32x4 v = xr[u];
-            if (kInt4) {
-                // sum of the 8 values, then over the 16 lanes that hold one scale group of one row
-                float sum = 0.f;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sum += __uint_as_float(v[i] << 16) + __uint_as_float(v[i] & 0xffff0000u);
-#pragma unroll
-                for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
-                if ((b & 15) == 0) sx[(b >> 4) * kRows + r] = -1.5f * sum;
-                // element order inside an 8-block follows the unpacked code order 0,4,1,5,2,6,3,7
-                u32x4 o4;
-                o4[0] = (v[0] & 0xffffu) | (v[2] << 16);
-                o4[1] = (v[0] >> 16) | (v[2] & 0xffff0000u);
-                o4[2] = (v[1] & 0xffffu) | (v[3] << 16);
-                o4[3] = (v[1] >> 16) | (v[3] & 0xffff0000u);
-                v = o4;
-            }
-            *(u32x4 *)(xs + r * kStride + b * 16) = v;
-        }
-    };
-    // packed weights (+ scales) of one chunk: lane (c,q) reads k in [128 g + 32 q, +32) of its rows
-    auto load_w = [&](WRegs<GC, kWH> &dst, int kc) {
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int gl = 0; gl < GC; ++gl) {
-                const int g = kc * GC + gl;
-                const bool ok = tile_ok[nt] && g < G;
-#pragma unroll
-                for (int h = 0; h < kWH; ++h) {
-                    dst.w[nt][gl][h] = u32x4{0, 0, 0, 0};
-                    if (ok) {
-                        const uint32_t *src = wrow[nt] + (kInt4 ? (g * 16 + q * 4) : (g * 32 + q * 8 + h * 4));
-                        dst.w[nt][gl][h] = __builtin_nontemporal_load((const u32x4 *)src);
-                    }
-                }
-                if (kInt4) {
-                    dst.s[nt][gl] = 0;
-                    if (ok) dst.s[nt][gl] = ((const uint16_t *)p.scales)[((int64_t)e * N + nrow[nt]) * G + g];
-                }
-            }
-    };
-
-    WRegs<GC, kWH> wcur, wnxt;
-    load_x(0);
-    load_w(wcur, 0);
-    for (int kc = 0; kc < n_chunks; ++kc) {
-        __syncthreads();  // the previous chunk's LDS readers are done
-        store_x();
-        __syncthreads();
-        if (kc + 1 < n_chunks) {
-            load_x(kc + 1);
-            load_w(wnxt, kc + 1);
-        }
-        const int ng = min(GC, G - kc * GC);
-#pragma unroll
-        for (int gl = 0; gl < GC; ++gl) {
-            if (gl < ng) {
-                f32x4 ag[2][MTC];
-                if (kInt4) {
-#pragma unroll
-                    for (int mt = 0; mt < MTC; ++mt) {
-                        const f32x4 init = *(const f32x4 *)(sx + gl * kRows + mt * 16 + 4 * q);
-                        ag[0][mt] = init;
-                        ag[1][mt] = init;
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (kInt4) {
-                        const bf16x8 b0 = unpack_int4_word(wcur.w[0][gl][0][j]);
-                        const bf16x8 b1 = unpack_int4_word(wcur.w[1][gl][0][j]);
-#pragma unroll
-                        for (int mt = 0; mt < MTC; ++mt) {
-                            const bf16x8 a =
-                                *(const bf16x8 *)(xs + (mt * 16 + c) * kStride + (gl * 128 + q * 32 + j * 8) * 2);
-                            ag[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b0, ag[0][mt], 0, 0, 0);
-                            ag[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b1, ag[1][mt], 0, 0, 0);
-                        }
-                    } else {
-                        const u32x4 w0 = wcur.w[0][gl][j >> 1], w1 = wcur.w[1][gl][j >> 1];
-                        const long b0 = (long)(((uint64_t)w0[(j & 1) * 2 + 1] << 32) | w0[(j & 1) * 2]);
-                        const long b1 = (long)(((uint64_t)w1[(j & 1) * 2 + 1] << 32) | w1[(j & 1) * 2]);
-#pragma unroll
-                        for (int mt = 0; mt < MTC; ++mt) {
-                            const long a = *(const long *)(xs + (mt * 16 + c) * kStride + gl * 128 + q * 32 + j * 8);
-                            acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a, b0, acc[0][mt], 0, 0, 0);
-                            acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a, b1, acc[1][mt], 0, 0, 0);
-                        }
-                    }
-                }
-                if (kInt4) {
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt) {
-                        const float s16 = 16.f * bf16_bits_to_f32(wcur.s[nt][gl]);
-#pragma unroll
-                        for (int mt = 0; mt < MTC; ++mt)
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) acc[nt][mt][i] = fmaf(s16, ag[nt][mt][i], acc[nt][mt][i]);
-                    }
-                }
-            }
-        }
-        if (kc + 1 < n_chunks) wcur = wnxt;
-    }
-
-    // epilogue: lane (c,q) holds rows 4q..4q+3 of each token tile, column c of each weight tile
-    float swn[2] = {1.f, 1.f};
-    if (!kInt4) {
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) swn[nt] = tile_ok[nt] ? ((const float *)p.scales)[(int64_t)e * N + nrow[nt]] : 0.f;
-    }
-#pragma unroll
-    for (int mt = 0; mt < MTC; ++mt) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = mt * 16 + 4 * q + i;
-            if (r < mrem) {
-                const int64_t srow = (int64_t)row0 + m0 + r;
-                const int64_t orow = p.out_row_map ? (int64_t)p.out_row_map[srow] : srow;
-                float v0 = acc[0][mt][i], v1 = acc[1][mt][i];
-                if (!kInt4) {
-                    const float sxr = p.x_scales[s_row[r]];
-                    v0 *= sxr * swn[0];
-                    v1 *= sxr * swn[1];
-                }
-                if (EPI == QARL_EPI_SILU_MUL) {
-                    if (tile_ok[0]) {
-                        const float a = v0 / (1.f + expf(-v0)) * v1;
-                        ((uint16_t *)p.out)[orow * (N / 2) + nrow[0]] = (uint16_t)f32_to_bf16_bits(a);
-                    }
-                } else if (p.out_f32) {
-                    if (tile_ok[0]) ((float *)p.out)[orow * N + nrow[0]] = v0;
-                    if (tile_ok[1]) ((float *)p.out)[orow * N + nrow[1]] = v1;
-                } else {
-                    if (tile_ok[0]) ((uint16_t *)p.out)[orow * N + nrow[0]] = (uint16_t)f32_to_bf16_bits(v0);
-                    if (tile_ok[1]) ((uint16_t *)p.out)[orow * N + nrow[1]] = (uint16_t)f32_to_bf16_bits(v1);
-                }
-            }
-        }
-    }
-}
-
-// MT = 16-row token tiles held per pass.  The host picks it from the mean rows per expert; an
-// expert with more rows than 16*MT takes further passes over its weights.
-template <int FMT, int EPI, int MT>
-__global__ __launch_bounds__(kSThreads, 2) void qgemm_stream_kernel(StreamParams p)
+// FMT: weight format; EPI: NONE or SILU_MUL; MT: 16-row token tiles per block; R: ring depth in
+// scale groups (must divide K/128).
+template <int FMT, int EPI, int MT, int R>
+__global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
-    constexpr int GC = (MT <= 2) ? 4 : 2;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = lane & 15;
-    const int e = blockIdx.y;
+    constexpr int kWH = kInt4 ? 1 : 2;  // 16-byte loads per lane, tile and group
+    constexpr int kRowsMax = MT * 16;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, q = lane >> 4;
+    const int N = p.N, K = p.K, G = K / kGroup;
+    const int stride = x_stride(kInt4, K);
+
+    // workgroup id -> (expert, slice, row block).  Ids go round-robin over the 8 XCDs; the row
+    // blocks of one (expert, slice) take consecutive positions on the same XCD.
+    const int xcd = blockIdx.x & 7, pos = blockIdx.x >> 3;
+    const int mh = pos % p.m_split;
+    const int unit_id = (pos / p.m_split) * 8 + xcd;
+    if (unit_id >= p.E * p.n_slices) return;
+    const int e = unit_id / p.n_slices, slice = unit_id % p.n_slices;
     const int row0 = p.offsets[e];
     const int Me = p.offsets[e + 1] - row0;
-    if (Me <= 0) return;
+    if (Me <= mh * kRowsMax) return;
 
-    const int N = p.N;
-    const int unit = blockIdx.x * kSWaves + wave;
-    const bool active = unit < p.n_units;
-    int nrow[2];  // weight rows of this lane's two tiles
-    if (EPI == QARL_EPI_SILU_MUL) {
-        nrow[0] = unit * 16 + c;
-        nrow[1] = N / 2 + unit * 16 + c;
-    } else {
-        nrow[0] = unit * 32 + c;
-        nrow[1] = unit * 32 + 16 + c;
-    }
-    bool tile_ok[2];
-    tile_ok[0] = active && nrow[0] - c + 16 <= N;
-    tile_ok[1] = active && nrow[1] - c + 16 <= N;
-    const int words_per_row = kInt4 ? p.K / 8 : p.K / 4;
-    const uint32_t *wrow[2];
+    int *s_row = (int *)smem;                              // [kRowsMax]
+    float *sx = (float *)(smem + kRowsMax * 4);            // int4: [G][kRowsMax]  -1.5 * group sums
+    unsigned char *xs = smem + kRowsMax * 4 + (kInt4 ? G * kRowsMax * 4 : 0);  // [kRowsMax][stride]
+
+    // this wavefront's pairs of weight tiles: units u_lo + wave, + 8, ...
+    const int per_slice = (p.n_units + p.n_slices - 1) / p.n_slices;
+    const int u_lo = slice * per_slice, u_hi = min(p.n_units, u_lo + per_slice);
+    const int n_my = (u_hi - u_lo - wave + kSWaves - 1) / kSWaves;  // may be <= 0
+    const int words_per_row = kInt4 ? K / 8 : K / 4;
+    const int64_t ebase = (int64_t)e * N;
+
+    auto tile_row = [&](int pi, int nt) -> int {  // weight row of this lane in tile nt of its pi-th pair
+        const int u = u_lo + wave + pi * kSWaves;
+        if (EPI == QARL_EPI_SILU_MUL) return (nt ? N / 2 : 0) + u * 16 + c;
+        return u * 32 + nt * 16 + c;
+    };
+
+    struct Slot {
+        u32x4 w[2][kWH];
+        uint32_t s[2];
+    };
+    Slot ring[R];
+    // Base pointers of the R-group batch (pair pi, groups g0..) of tile nt.  Past this wavefront's
+    // work they fall back to the start of the expert's codes: the ring is refilled without a
+    // branch (a conditional refill turns every slot into a merge of old and new value and doubles the
+    // registers the ring takes), and those few loads all hit one cached line.
+    auto batch_src = [&](int pi, int g0, int nt, const uint32_t *&src, const uint16_t *&ssrc) {
+        const bool ok = pi < n_my;
+        const int64_t row = ebase + (ok ? tile_row(pi, nt) : 0);
+        src = p.codes + row * words_per_row + (ok ? (kInt4 ? (g0 * 16 + q * 4) : (g0 * 32 + q * 8)) : 0);
+        ssrc = (const uint16_t *)p.scales + (kInt4 ? row * G + (ok ? g0 : 0) : 0);
+    };
+    auto fill = [&](Slot &dst, int r, const uint32_t *const (&src)[2], const uint16_t *const (&ssrc)[2]) {
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-        wrow[nt] = p.codes + ((int64_t)e * N + (tile_ok[nt] ? nrow[nt] : 0)) * words_per_row;
+        for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+            for (int h = 0; h < kWH; ++h)
+                dst.w[nt][h] = __builtin_nontemporal_load((const u32x4 *)(src[nt] + r * (kInt4 ? 16 : 32) + h * 4));
+            if (kInt4) dst.s[nt] = ssrc[nt][r];
+        }
+    };
+    auto fill_ring = [&](int pi, int g0) {
+        const uint32_t *src[2];
+        const uint16_t *ssrc[2];
+        batch_src(pi, g0, 0, src[0], ssrc[0]);
+        batch_src(pi, g0, 1, src[1], ssrc[1]);
+#pragma unroll
+        for (int r = 0; r < R; ++r) fill(ring[r], r, src, ssrc);
+    };
+    // fill the ring before anything else so the weight stream starts while x is being staged
+    fill_ring(0, 0);
 
-    for (int m0 = 0; m0 < Me; m0 += MT * 16)
-        stream_pass<FMT, EPI, MT, GC>(p, smem, e, row0, m0, min(MT * 16, Me - m0), nrow, tile_ok, wrow);
+    for (int m0 = mh * kRowsMax; m0 < Me; m0 += kRowsMax * p.m_split) {
+        const int mrem = min(kRowsMax, Me - m0);
+        __syncthreads();  // previous pass is done with the LDS tile
+        if (tid < kRowsMax) {
+            const int i = row0 + m0 + tid;
+            s_row[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
+        }
+        __syncthreads();
+        // ---- gather the token rows into LDS (whole K), 16-byte blocks, row-major
+        {
+            const int blk_per_row = kInt4 ? K / 8 : K / 16;
+            const int total = kRowsMax * blk_per_row;
+            for (int base = 0; base < total; base += kSThreads * 4) {
+                u32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = base + u * kSThreads + tid;
+                    v[u] = u32x4{0, 0, 0, 0};
+                    if (idx < total) {
+                        const int r = idx / blk_per_row, b = idx % blk_per_row;
+                        const int xrow = s_row[r];
+                        if (xrow >= 0)
+                            v[u] = *(const u32x4 *)((const unsigned char *)p.x +
+                                                    (int64_t)xrow * K * (kInt4 ? 2 : 1) + b * 16);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = base + u * kSThreads + tid;
+                    const int r = idx / blk_per_row, b = idx % blk_per_row;
+                    u32x4 o4 = v[u];
+                    if (kInt4) {
+                        // sum of the 8 values, then over the 16 lanes that hold one scale group of one row
+                        float sum = 0.f;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            sum += __uint_as_float(v[u][i] << 16) + __uint_as_float(v[u][i] & 0xffff0000u);
+#pragma unroll
+                        for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
+                        if (idx < total && (b & 15) == 0) sx[(b >> 4) * kRowsMax + r] = -1.5f * sum;
+                        // element order inside an 8-block follows the unpacked code order 0,4,1,5,2,6,3,7
+                        o4[0] = (v[u][0] & 0xffffu) | (v[u][2] << 16);
+                        o4[1] = (v[u][0] >> 16) | (v[u][2] & 0xffff0000u);
+                        o4[2] = (v[u][1] & 0xffffu) | (v[u][3] << 16);
+                        o4[3] = (v[u][1] >> 16) | (v[u][3] & 0xffff0000u);
+                    }
+                    if (idx < total) *(u32x4 *)(xs + r * stride + b * 16) = o4;
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- stream this wavefront's weight tiles
+        for (int pi = 0; pi < n_my; ++pi) {
+            f32x4 acc[2][MT];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int g0 = 0; g0 < G; g0 += R) {
+                // the batch that refills the ring while this one is consumed: same pair or the next one
+                const bool same = g0 + R < G;
+                const uint32_t *nsrc[2];
+                const uint16_t *nssrc[2];
+                batch_src(same ? pi : pi + 1, same ? g0 + R : 0, 0, nsrc[0], nssrc[0]);
+                batch_src(same ? pi : pi + 1, same ? g0 + R : 0, 1, nsrc[1], nssrc[1]);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int g = g0 + r;
+                    Slot &cur = ring[r];
+                    // The LDS tile does not change while the tiles stream, so the optimizer would hoist
+                    // its reads out of the pair loop into hundreds of registers; pin them to their group.
+                    asm volatile("" ::: "memory");
+                    if (kInt4) {
+                        f32x4 ag[2][MT];
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) {
+                            const f32x4 init = *(const f32x4 *)(sx + g * kRowsMax + mt * 16 + 4 * q);
+                            ag[0][mt] = init;
+                            ag[1][mt] = init;
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const bf16x8 b0 = unpack_int4_word(cur.w[0][0][j]);
+                            const bf16x8 b1 = unpack_int4_word(cur.w[1][0][j]);
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt) {
+                                const bf16x8 a = *(const bf16x8 *)(xs + (mt * 16 + c) * stride +
+                                                                   (g * 128 + q * 32 + j * 8) * 2);
+                                ag[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b0, ag[0][mt], 0, 0, 0);
+                                ag[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b1, ag[1][mt], 0, 0, 0);
+                            }
+                        }
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt) {
+                            const float s16 = 16.f * bf16_bits_to_f32(cur.s[nt]);
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) acc[nt][mt][i] = fmaf(s16, ag[nt][mt][i], acc[nt][mt][i]);
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const u32x4 w0 = cur.w[0][j >> 1], w1 = cur.w[1][j >> 1];
+                            const long b0 = (long)(((uint64_t)w0[(j & 1) * 2 + 1] << 32) | w0[(j & 1) * 2]);
+                            const long b1 = (long)(((uint64_t)w1[(j & 1) * 2 + 1] << 32) | w1[(j & 1) * 2]);
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt) {
+                                const long a = *(const long *)(xs + (mt * 16 + c) * stride + g * 128 + q * 32 + j * 8);
+                                acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a, b0, acc[0][mt], 0, 0, 0);
+                                acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a, b1, acc[1][mt], 0, 0, 0);
+                            }
+                        }
+                    }
+                    // refill this slot with the group R ahead
+                    fill(cur, r, nsrc, nssrc);
+                    // keep the groups apart in the schedule: hoisting the next group's LDS reads and
+                    // code expansion over this one only costs registers the ring needs
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // ---- epilogue of this pair: lane (c,q) holds rows 4q..4q+3 of each token tile, column c
+            const int n0 = tile_row(pi, 0), n1 = tile_row(pi, 1);
+            float sw0 = 1.f, sw1 = 1.f;
+            if (!kInt4) {
+                sw0 = ((const float *)p.scales)[ebase + n0];
+                sw1 = ((const float *)p.scales)[ebase + n1];
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int r = mt * 16 + 4 * q + i;
+                    if (r < mrem) {
+                        const int64_t srow = (int64_t)row0 + m0 + r;
+                        const int64_t orow = p.out_row_map ? (int64_t)p.out_row_map[srow] : srow;
+                        float v0 = acc[0][mt][i], v1 = acc[1][mt][i];
+                        if (!kInt4) {
+                            const float sxr = p.x_scales[s_row[r]];
+                            v0 *= sxr * sw0;
+                            v1 *= sxr * sw1;
+                        }
+                        if (EPI == QARL_EPI_SILU_MUL) {
+                            const float a = v0 / (1.f + expf(-v0)) * v1;
+                            ((uint16_t *)p.out)[orow * (N / 2) + n0] = (uint16_t)f32_to_bf16_bits(a);
+                        } else if (p.out_f32) {
+                            ((float *)p.out)[orow * N + n0] = v0;
+                            ((float *)p.out)[orow * N + n1] = v1;
+                        } else {
+                            ((uint16_t *)p.out)[orow * N + n0] = (uint16_t)f32_to_bf16_bits(v0);
+                            ((uint16_t *)p.out)[orow * N + n1] = (uint16_t)f32_to_bf16_bits(v1);
+                        }
+                    }
+                }
+            }
+        }
+        // a further pass over the same tiles: restart the ring at this wavefront's first pair
+        if (m0 + kRowsMax * p.m_split < Me) fill_ring(0, 0);
+    }
 }
 
-template <int FMT, int EPI, int MT>
-static int launch_mt(const StreamParams &p, int E, hipStream_t s)
+template <int FMT, int EPI, int MT, int R>
+static int launch_cfg(const StreamParams &p, hipStream_t s)
 {
     constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
-    constexpr int GC = (MT <= 2) ? 4 : 2;
-    const size_t lds = (size_t)MT * 16 * x_stride(kInt4, GC) + (size_t)kMaxGC * kRows * 4 + kRows * 4;
-    static bool attr_done = false;
-    auto kern = qgemm_stream_kernel<FMT, EPI, MT>;
-    if (!attr_done) {
+    const int G = p.K / kGroup;
+    const size_t lds = (size_t)MT * 16 * 4 + (kInt4 ? (size_t)G * MT * 16 * 4 : 0) + (size_t)MT * 16 * x_stride(kInt4, p.K);
+    if (lds > 160 * 1024) {
+        set_error("qgemm (decode path): K=%d needs %zu bytes of LDS per workgroup, more than the 160 KiB of a CU", p.K, lds);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    static size_t attr_lds = 0;
+    auto kern = qgemm_stream_kernel<FMT, EPI, MT, R>;
+    if (lds > attr_lds) {
         int rc = check_hip(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
                            "hipFuncSetAttribute(stream)");
         if (rc) return rc;
-        attr_done = true;
+        attr_lds = lds;
     }
-    dim3 grid((p.n_units + kSWaves - 1) / kSWaves, E);
-    kern<<<grid, dim3(kSThreads), lds, s>>>(p);
+    const int64_t units = (int64_t)p.E * p.n_slices;
+    const int64_t grid = ((units + 7) / 8) * 8 * p.m_split;
+    kern<<<dim3((unsigned)grid), dim3(kSThreads), lds, s>>>(p);
     return check_hip(hipGetLastError(), "qgemm_stream_kernel");
+}
+
+template <int FMT, int EPI, int MT>
+static int launch_ring(const StreamParams &p, hipStream_t s)
+{
+    const int G = p.K / kGroup;
+    // ring depth: the deepest that divides K/128 and still fits the register file beside the accumulators
+    if (MT <= 2 && G % 8 == 0) return launch_cfg<FMT, EPI, MT, 8>(p, s);
+    if (MT <= 2 && G % 6 == 0) return launch_cfg<FMT, EPI, MT, 6>(p, s);
+    if (G % 4 == 0) return launch_cfg<FMT, EPI, MT, 4>(p, s);
+    if (G % 3 == 0) return launch_cfg<FMT, EPI, MT, 3>(p, s);
+    if (G % 2 == 0) return launch_cfg<FMT, EPI, MT, 2>(p, s);
+    return launch_cfg<FMT, EPI, MT, 1>(p, s);
 }
 
 template <int FMT, int EPI>
 static int launch_one(const GemmArgs &a, hipStream_t s)
 {
+    constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
     StreamParams p;
     p.codes = (const uint32_t *)a.codes;
     p.scales = a.scales;
@@ -327,20 +349,42 @@ static int launch_one(const GemmArgs &a, hipStream_t s)
     p.out_row_map = a.out_row_map;
     p.offsets = a.offsets;
     p.out = a.out;
+    p.E = a.E;
     p.N = a.N;
     p.K = a.K;
     p.out_f32 = a.out_f32;
-    p.n_units = (EPI == QARL_EPI_SILU_MUL) ? (a.N / 2) / 16 : (a.N + 31) / 32;
-    // token tiles per pass from the mean rows per expert (mean + 4 sigma of a uniform router fits)
+    p.n_units = (EPI == QARL_EPI_SILU_MUL) ? (a.N / 2) / 16 : a.N / 32;
+    // rows per expert the grid should cover in one pass: mean + 4 sigma of a uniform router
     const double mean = (double)a.M / (double)a.E;
     const double need = mean + 4.0 * sqrt(mean);
-    if (need <= 16.0) return launch_mt<FMT, EPI, 1>(p, a.E, s);
-    if (need <= 32.0) return launch_mt<FMT, EPI, 2>(p, a.E, s);
-    return launch_mt<FMT, EPI, 4>(p, a.E, s);
+    // token tiles per workgroup: limited by the LDS tile, which holds the whole K of every row
+    const int row_bytes = x_stride(kInt4, a.K) + (kInt4 ? (a.K / kGroup) * 4 : 0) + 4;
+    const int mt_fit = (150 * 1024) / (16 * row_bytes);
+    if (mt_fit < 1) {
+        set_error("qgemm (decode path): K=%d does not fit the LDS tile", a.K);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    int MT = need <= 16.0 ? 1 : ((need <= 32.0 || mt_fit < 4) ? 2 : 4);
+    if (MT > mt_fit) MT = 1;
+    const int ms = (int)ceil(need / (16.0 * MT));
+    p.m_split = ms < 1 ? 1 : (ms > 4 ? 4 : ms);
+    // slices per expert: aim at one workgroup per CU, at least one pair of tiles per wavefront
+    int slices = (256 + a.E * p.m_split - 1) / (a.E * p.m_split);
+    const int max_slices = (p.n_units + kSWaves - 1) / kSWaves;
+    if (slices > max_slices) slices = max_slices;
+    if (slices < 1) slices = 1;
+    p.n_slices = slices;
+    if (MT == 1) return launch_ring<FMT, EPI, 1>(p, s);
+    if (MT == 2) return launch_ring<FMT, EPI, 2>(p, s);
+    return launch_ring<FMT, EPI, 4>(p, s);
 }
 
 int launch_qgemm_stream(const GemmArgs &a, hipStream_t s)
 {
+    if (a.N % 32 != 0) {
+        set_error("qgemm (decode path): N %% 32 == 0 required (got %d)", a.N);
+        return QARL_ERR_UNSUPPORTED;
+    }
     if (a.fmt == QARL_W4A16_G128)
         return a.epilogue == QARL_EPI_SILU_MUL ? launch_one<QARL_W4A16_G128, QARL_EPI_SILU_MUL>(a, s)
                                                : launch_one<QARL_W4A16_G128, QARL_EPI_NONE>(a, s);

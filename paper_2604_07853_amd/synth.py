@@ -75,7 +75,7 @@ def expert_weights(n_experts, hidden, inter, seed, device="cpu", std=0.02):
 
 def perturb(w, std, seed):
     """Simulated optimizer update: bf16(float(w) + N(0, std))."""
-    g = _gen(seed, w.device.type if w.device.type != "cuda" else w.device)
+    g = _gen(seed, w.device)
     n = torch.randn(w.shape, generator=g, device=w.device, dtype=torch.float32) * std
     return (w.float() + n).to(torch.bfloat16)
 
