@@ -56,12 +56,14 @@ typedef enum {
 typedef enum { QARL_OUT_BF16 = 0, QARL_OUT_F32 = 1 } qarl_out_dtype;
 
 /* Quantized weights of E matrices [N][K] (K contiguous).  Host struct, device buffers.
- *   W4A16_G128: codes  uint32 [E][N][K/8]; element 8*j+i of a row sits in bits [4i,4i+3] of
- *                      word j as q+8, q in [-8,7];
+ *   W4A16_G128: codes  uint32, E*N*K/8 words in 1 KiB blocks of 16 rows x 128 k (one scale group
+ *                      of 16 consecutive rows), the unit a wavefront of the GEMM kernels loads:
+ *                      [E*N/16 row tiles][K/128 groups][4 (k%128)/32][16 n%16][4 (k%32)/8] words;
+ *                      element k%8 = i of a word sits in its bits [4i,4i+3] as q+8, q in [-8,7];
  *               scales bf16   [E][N][K/128]; dequantized weight = float(scale) * q, exact in
  *                      fp32 and never rounded to 16 bits.
  *   FP8_E4M3_CH: codes uint8  [E][N][K] (e4m3 bit patterns); scales float [E][N].
- * Requirements: K % 128 == 0, N % 16 == 0, buffers 16-byte aligned. */
+ * Requirements: K % 128 == 0, N % 32 == 0, buffers 16-byte aligned. */
 typedef struct {
     int32_t fmt; /* qarl_format */
     int32_t E, N, K;
@@ -118,7 +120,8 @@ int qarl_moe_route(const void *logits_bf16, int T, int E, int topk, int renorm, 
  *                        token in slot order with weights combine_w [T][topk]; sorted_pairs as
  *                        written by qarl_moe_route
  *   out_dtype  QARL_OUT_BF16 or QARL_OUT_F32 (SILU_MUL: bf16 only)
- *   path       AUTO picks DECODE when the mean rows per expert is small
+ *   path       AUTO picks DECODE when the mean rows per expert is small and the shape fits it
+ *              (DECODE keeps whole rows of x in LDS: W4A16 needs K % 256 == 0 and K <= 2048)
  * Errors: INVALID_ARG, ALIGNMENT, UNSUPPORTED (shape outside the kernels' domain),
  * WORKSPACE (ws too small).  M == 0 is a no-op (COMBINE still zero-fills out). */
 int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scales, int64_t x_rows,

@@ -39,8 +39,8 @@ static int check_qweight(const qarl_qweight *w, const char *who)
         set_error("%s: E, N, K must be positive (got %d, %d, %d)", who, w->E, w->N, w->K);
         return QARL_ERR_INVALID_ARG;
     }
-    if (w->K % 128 != 0 || w->N % 16 != 0) {
-        set_error("%s: need K %% 128 == 0 and N %% 16 == 0 (got N=%d, K=%d)", who, w->N, w->K);
+    if (w->K % 128 != 0 || w->N % 32 != 0) {
+        set_error("%s: need K %% 128 == 0 and N %% 32 == 0 (got N=%d, K=%d)", who, w->N, w->K);
         return QARL_ERR_UNSUPPORTED;
     }
     if (w->fmt == QARL_W4A16_G128 && w->group != 128) {
@@ -229,7 +229,8 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
         a.out_row_map = sorted_pairs;  // Y lands in pair order: row t*topk + slot
     }
     int use = path;
-    if (use == QARL_PATH_AUTO) use = (M <= (int64_t)W->E * 64) ? QARL_PATH_DECODE : QARL_PATH_PREFILL;
+    if (use == QARL_PATH_AUTO)
+        use = (M <= (int64_t)W->E * 64 && qgemm_stream_supported(W->fmt, W->N, W->K)) ? QARL_PATH_DECODE : QARL_PATH_PREFILL;
     rc = (use == QARL_PATH_DECODE) ? launch_qgemm_stream(a, st) : launch_qgemm_tile(a, st);
     if (rc) return rc;
     if (epilogue == QARL_EPI_COMBINE)

@@ -42,6 +42,29 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// (a & mask) | c in one VALU op.  The compiler splits it into v_and + v_or when mask and c are
+// literals (a VOP3 encoding takes no literal on this target), so the operands are pinned to registers.
+__device__ __forceinline__ uint32_t and_or_b32(uint32_t a, uint32_t mask, uint32_t c)
+{
+    uint32_t d;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(c));
+    return d;
+}
+
+// One packed word of eight int4 codes (element i in bits [4i,4i+3], stored as q+8) -> eight exact
+// bf16 values (q+24)/16 in the order c0,c4,c1,c5,c2,c6,c3,c7: the nibble lands in the top four
+// mantissa bits of bf16 1.0.  One shift and one and-or per pair of codes.
+__device__ __forceinline__ bf16x8 unpack_int4_word(uint32_t w)
+{
+    const uint32_t mask = 0x00780078u, one = 0x3f803f80u;
+    u32x4 d;
+    d[0] = and_or_b32(w << 3, mask, one);
+    d[1] = and_or_b32(w >> 1, mask, one);
+    d[2] = and_or_b32(w >> 5, mask, one);
+    d[3] = and_or_b32(w >> 9, mask, one);
+    return __builtin_bit_cast(bf16x8, d);
+}
+
 // Host-side error plumbing (api.hip).
 void set_error(const char *fmt, ...);
 int check_hip(hipError_t e, const char *what);
@@ -68,6 +91,7 @@ struct GemmArgs {
     int out_f32;
 };
 int launch_qgemm_stream(const GemmArgs &a, hipStream_t s);
+bool qgemm_stream_supported(int fmt, int N, int K);
 int launch_qgemm_tile(const GemmArgs &a, hipStream_t s);
 int launch_combine(const float *y_pair_order, const float *w, int T, int topk, int N, void *out, int out_f32,
                    hipStream_t s);

@@ -8,8 +8,11 @@
 // that single barrier every wavefront runs on its own: it walks its pairs of 16-row weight
 // tiles and, per pair, the K/128 scale groups, with the packed codes of the next R groups
 // always in flight in a register ring (global -> registers, one 16-byte load per lane,
-// tile and group).  Codes are expanded in registers to bf16 MFMA operands and meet the
-// token rows from LDS in v_mfma_f32_16x16x32.
+// tile and group; the int4 codes are stored in 1 KiB blocks of 16 rows x 128 k, so such a
+// wavefront load is one contiguous KiB and a tile's whole K a contiguous stream).  The bf16
+// scales of a pair travel once through a small per-wavefront LDS buffer, one pair ahead.
+// Codes are expanded in registers to bf16 MFMA operands and meet the token rows from LDS in
+// v_mfma_f32_16x16x32.
 //
 // W4A16 numerics: the dequantized weight is s*q exactly.  The nibble u = q+8 is placed in
 // the top mantissa bits of bf16 1.0, giving the exact bf16 value (q+24)/16 with one shift
@@ -45,19 +48,15 @@ struct StreamParams {
     int m_split;     // row blocks per (expert, slice) in the grid
 };
 
-__device__ __forceinline__ bf16x8 unpack_int4_word(uint32_t w)
-{
-    // -> bf16 pairs (c0,c4) (c1,c5) (c2,c6) (c3,c7), each (q+24)/16
-    u32x4 d;
-    d[0] = ((w << 3) & 0x00780078u) | 0x3f803f80u;
-    d[1] = ((w >> 1) & 0x00780078u) | 0x3f803f80u;
-    d[2] = ((w >> 5) & 0x00780078u) | 0x3f803f80u;
-    d[3] = ((w >> 9) & 0x00780078u) | 0x3f803f80u;
-    return __builtin_bit_cast(bf16x8, d);
-}
-
 // LDS bytes per activation row: the row plus 16 bytes, so consecutive rows skew by 4 banks.
 __host__ __device__ constexpr int x_stride(bool int4, int K) { return K * (int4 ? 2 : 1) + 16; }
+
+// Dynamic LDS of a workgroup: row ids, int4 group sums, int4 per-wavefront scale buffers, token tile.
+static size_t stream_lds_bytes(bool int4, int K, int MT)
+{
+    const size_t G = K / kGroup, rows = (size_t)MT * 16;
+    return rows * 4 + (int4 ? G * rows * 4 + (size_t)kSWaves * 2 * 32 * G * 2 : 0) + rows * x_stride(int4, K);
+}
 
 // FMT: weight format; EPI: NONE or SILU_MUL; MT: 16-row token tiles per block; R: ring depth in
 // scale groups (must divide K/128).
@@ -81,13 +80,12 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
     const int unit_id = (pos / p.m_split) * 8 + xcd;
     if (unit_id >= p.E * p.n_slices) return;
     const int e = unit_id / p.n_slices, slice = unit_id % p.n_slices;
-    const int row0 = p.offsets[e];
-    const int Me = p.offsets[e + 1] - row0;
-    if (Me <= mh * kRowsMax) return;
 
     int *s_row = (int *)smem;                              // [kRowsMax]
     float *sx = (float *)(smem + kRowsMax * 4);            // int4: [G][kRowsMax]  -1.5 * group sums
-    unsigned char *xs = smem + kRowsMax * 4 + (kInt4 ? G * kRowsMax * 4 : 0);  // [kRowsMax][stride]
+    // int4: per wavefront two buffers of [2 tiles][16 rows][G] bf16 scales (this pair, next pair)
+    uint16_t *ssc = (uint16_t *)(smem + kRowsMax * 4 + (kInt4 ? G * kRowsMax * 4 : 0)) + (kInt4 ? wave * 2 * 32 * G : 0);
+    unsigned char *xs = smem + kRowsMax * 4 + (kInt4 ? G * kRowsMax * 4 + kSWaves * 2 * 32 * G * 2 : 0);  // [kRowsMax][stride]
 
     // this wavefront's pairs of weight tiles: units u_lo + wave, + 8, ...
     const int per_slice = (p.n_units + p.n_slices - 1) / p.n_slices;
@@ -104,93 +102,159 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
 
     struct Slot {
         u32x4 w[2][kWH];
-        uint32_t s[2];
     };
     Slot ring[R];
-    // Base pointers of the R-group batch (pair pi, groups g0..) of tile nt.  Past this wavefront's
-    // work they fall back to the start of the expert's codes: the ring is refilled without a
-    // branch (a conditional refill turns every slot into a merge of old and new value and doubles the
-    // registers the ring takes), and those few loads all hit one cached line.
-    auto batch_src = [&](int pi, int g0, int nt, const uint32_t *&src, const uint16_t *&ssrc) {
-        const bool ok = pi < n_my;
-        const int64_t row = ebase + (ok ? tile_row(pi, nt) : 0);
-        src = p.codes + row * words_per_row + (ok ? (kInt4 ? (g0 * 16 + q * 4) : (g0 * 32 + q * 8)) : 0);
-        ssrc = (const uint16_t *)p.scales + (kInt4 ? row * G + (ok ? g0 : 0) : 0);
+    // Base pointer of the R-group batch (pair pi, groups g0..) of tile nt for this lane.  int4: the
+    // codes of (16-row tile, group) are one 1 KiB block, lane l owns bytes [16 l, 16 l + 16), the blocks
+    // of a tile follow each other along K.  fp8: row-major bytes, lane (c,q) reads k in [32 q, +32).
+    // Past this wavefront's work the pointer falls back to the start of the expert's codes: the ring
+    // is refilled without a branch (a conditional refill turns every slot into a merge of old and new
+    // value and doubles the registers the ring takes), and those few loads all hit one cached line.
+    auto pair_tile16 = [&](int pi, int nt) -> int {  // index of the 16-row tile nt of this wavefront's pi-th pair
+        const int u = u_lo + wave + pi * kSWaves;
+        if (EPI == QARL_EPI_SILU_MUL) return (nt ? (N / 2) / 16 : 0) + u;
+        return u * 2 + nt;
     };
-    auto fill = [&](Slot &dst, int r, const uint32_t *const (&src)[2], const uint16_t *const (&ssrc)[2]) {
+    auto batch_src = [&](int pi, int g0, int nt) -> const uint32_t * {
+        const bool ok = pi < n_my;
+        if (kInt4) {
+            const int64_t tile = ebase / 16 + (ok ? pair_tile16(pi, nt) : 0);
+            return p.codes + (tile * G + (ok ? g0 : 0)) * 256 + lane * 4;
+        }
+        const int64_t row = ebase + (ok ? pair_tile16(pi, nt) * 16 + c : 0);
+        return p.codes + row * words_per_row + (ok ? g0 * 32 + q * 8 : 0);
+    };
+    auto fill = [&](Slot &dst, int r, const uint32_t *const (&src)[2]) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
             for (int h = 0; h < kWH; ++h)
-                dst.w[nt][h] = __builtin_nontemporal_load((const u32x4 *)(src[nt] + r * (kInt4 ? 16 : 32) + h * 4));
-            if (kInt4) dst.s[nt] = ssrc[nt][r];
-        }
+                dst.w[nt][h] = __builtin_nontemporal_load((const u32x4 *)(src[nt] + r * (kInt4 ? 256 : 32) + h * 4));
     };
     auto fill_ring = [&](int pi, int g0) {
-        const uint32_t *src[2];
-        const uint16_t *ssrc[2];
-        batch_src(pi, g0, 0, src[0], ssrc[0]);
-        batch_src(pi, g0, 1, src[1], ssrc[1]);
+        const uint32_t *src[2] = {batch_src(pi, g0, 0), batch_src(pi, g0, 1)};
 #pragma unroll
-        for (int r = 0; r < R; ++r) fill(ring[r], r, src, ssrc);
+        for (int r = 0; r < R; ++r) fill(ring[r], r, src);
     };
-    // fill the ring before anything else so the weight stream starts while x is being staged
+    // int4 scales of a pair: [2 tiles][16 rows][G] bf16 = 16 G dwords, fetched by the wavefront as
+    // dwords (lane l takes dwords l, l + 64, ...) and parked in its LDS buffer one pair ahead.
+    constexpr int kScRegs = 4;  // dwords per lane: covers G <= 16
+    uint32_t scr[kScRegs];
+    auto load_scales = [&](int pi) {
+        if (kInt4) {
+            const int half = G / 2;  // dwords per row
+#pragma unroll
+            for (int u = 0; u < kScRegs; ++u) {
+                const int d = u * 64 + lane;
+                scr[u] = 0;
+                if (pi < n_my && d < 32 * half) {
+                    const int nt = d / (16 * half), rr = (d / half) % 16, dw = d % half;
+                    const int64_t row = ebase + pair_tile16(pi, nt) * 16 + rr;
+                    scr[u] = ((const uint32_t *)p.scales)[(row * G) / 2 + dw];
+                }
+            }
+        }
+    };
+    auto park_scales = [&](int buf) {
+        if (kInt4) {
+            const int half = G / 2;
+#pragma unroll
+            for (int u = 0; u < kScRegs; ++u) {
+                const int d = u * 64 + lane;
+                if (d < 32 * half) ((uint32_t *)(ssc + buf * 32 * G))[d] = scr[u];
+            }
+        }
+    };
+
+    // Start the weight stream at once: its addresses do not depend on the routing, and the first
+    // KiBs arrive while the row ids are looked up and the token tile is built.
+    load_scales(0);
     fill_ring(0, 0);
 
+    const int row0 = p.offsets[e];
+    const int Me = p.offsets[e + 1] - row0;
+    if (Me <= mh * kRowsMax) return;
+
+    bool first_pass = true;
     for (int m0 = mh * kRowsMax; m0 < Me; m0 += kRowsMax * p.m_split) {
         const int mrem = min(kRowsMax, Me - m0);
         __syncthreads();  // previous pass is done with the LDS tile
+        if (!first_pass) {
+            load_scales(0);
+            fill_ring(0, 0);
+        }
+        first_pass = false;
         if (tid < kRowsMax) {
             const int i = row0 + m0 + tid;
             s_row[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
         }
         __syncthreads();
-        // ---- gather the token rows into LDS (whole K), 16-byte blocks, row-major
+        // ---- gather the token rows into LDS (whole K) in 16-byte blocks.  A thread keeps one block
+        // column and walks down the rows, so the only index arithmetic is an add per block.
         {
-            const int blk_per_row = kInt4 ? K / 8 : K / 16;
-            const int total = kRowsMax * blk_per_row;
-            for (int base = 0; base < total; base += kSThreads * 4) {
-                u32x4 v[4];
+            const int bpr = kInt4 ? K / 8 : K / 16;      // blocks per row
+            const int rpp = kSThreads / bpr;             // rows covered per sweep of the workgroup
+            const int rsub = tid / bpr, b = tid - rsub * bpr;
+            if (rsub < rpp) {
+                constexpr int kBatch = 8;
+                for (int rb = rsub; rb < kRowsMax; rb += rpp * kBatch) {
+                    u32x4 v[kBatch];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int idx = base + u * kSThreads + tid;
-                    v[u] = u32x4{0, 0, 0, 0};
-                    if (idx < total) {
-                        const int r = idx / blk_per_row, b = idx % blk_per_row;
-                        const int xrow = s_row[r];
-                        if (xrow >= 0)
-                            v[u] = *(const u32x4 *)((const unsigned char *)p.x +
-                                                    (int64_t)xrow * K * (kInt4 ? 2 : 1) + b * 16);
+                    for (int u = 0; u < kBatch; ++u) {
+                        const int r = rb + u * rpp;
+                        v[u] = u32x4{0, 0, 0, 0};
+                        if (r < kRowsMax) {
+                            const int xrow = s_row[r];
+                            if (xrow >= 0)
+                                v[u] = *(const u32x4 *)((const unsigned char *)p.x +
+                                                        (int64_t)xrow * K * (kInt4 ? 2 : 1) + b * 16);
+                        }
                     }
-                }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int idx = base + u * kSThreads + tid;
-                    const int r = idx / blk_per_row, b = idx % blk_per_row;
-                    u32x4 o4 = v[u];
-                    if (kInt4) {
-                        // sum of the 8 values, then over the 16 lanes that hold one scale group of one row
-                        float sum = 0.f;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            sum += __uint_as_float(v[u][i] << 16) + __uint_as_float(v[u][i] & 0xffff0000u);
-#pragma unroll
-                        for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
-                        if (idx < total && (b & 15) == 0) sx[(b >> 4) * kRowsMax + r] = -1.5f * sum;
-                        // element order inside an 8-block follows the unpacked code order 0,4,1,5,2,6,3,7
-                        o4[0] = (v[u][0] & 0xffffu) | (v[u][2] << 16);
-                        o4[1] = (v[u][0] >> 16) | (v[u][2] & 0xffff0000u);
-                        o4[2] = (v[u][1] & 0xffffu) | (v[u][3] << 16);
-                        o4[3] = (v[u][1] >> 16) | (v[u][3] & 0xffff0000u);
+                    for (int u = 0; u < kBatch; ++u) {
+                        const int r = rb + u * rpp;
+                        u32x4 o4 = v[u];
+                        if (kInt4) {
+                            // element order inside an 8-block follows the unpacked code order 0,4,1,5,2,6,3,7
+                            o4[0] = __builtin_amdgcn_perm(v[u][2], v[u][0], 0x05040100u);
+                            o4[1] = __builtin_amdgcn_perm(v[u][2], v[u][0], 0x07060302u);
+                            o4[2] = __builtin_amdgcn_perm(v[u][3], v[u][1], 0x05040100u);
+                            o4[3] = __builtin_amdgcn_perm(v[u][3], v[u][1], 0x07060302u);
+                        }
+                        if (r < kRowsMax) *(u32x4 *)(xs + r * stride + b * 16) = o4;
                     }
-                    if (idx < total) *(u32x4 *)(xs + r * stride + b * 16) = o4;
                 }
             }
         }
+        park_scales(0);
         __syncthreads();
+        if (kInt4) {
+            // ---- group sums of the token rows, sx[g][m] = -1.5 * sum_k x[m][k], with the matrix core:
+            // x times a matrix of ones; every column of the product holds the sums.
+            const u32x4 ones4 = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+            const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+            for (int g = wave; g < G; g += kSWaves) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const bf16x8 a = *(const bf16x8 *)(xs + (mt * 16 + c) * stride + (g * 128 + q * 32 + j * 8) * 2);
+                        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, d, 0, 0, 0);
+                    }
+                    if (c == 0) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) d[i] *= -1.5f;
+                        *(f32x4 *)(sx + g * kRowsMax + mt * 16 + 4 * q) = d;
+                    }
+                }
+            }
+            __syncthreads();
+        }
 
         // ---- stream this wavefront's weight tiles
         for (int pi = 0; pi < n_my; ++pi) {
+            load_scales(pi + 1);
             f32x4 acc[2][MT];
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
@@ -199,17 +263,12 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
             for (int g0 = 0; g0 < G; g0 += R) {
                 // the batch that refills the ring while this one is consumed: same pair or the next one
                 const bool same = g0 + R < G;
-                const uint32_t *nsrc[2];
-                const uint16_t *nssrc[2];
-                batch_src(same ? pi : pi + 1, same ? g0 + R : 0, 0, nsrc[0], nssrc[0]);
-                batch_src(same ? pi : pi + 1, same ? g0 + R : 0, 1, nsrc[1], nssrc[1]);
+                const uint32_t *nsrc[2] = {batch_src(same ? pi : pi + 1, same ? g0 + R : 0, 0),
+                                           batch_src(same ? pi : pi + 1, same ? g0 + R : 0, 1)};
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     const int g = g0 + r;
                     Slot &cur = ring[r];
-                    // The LDS tile does not change while the tiles stream, so the optimizer would hoist
-                    // its reads out of the pair loop into hundreds of registers; pin them to their group.
-                    asm volatile("" ::: "memory");
                     if (kInt4) {
                         f32x4 ag[2][MT];
 #pragma unroll
@@ -232,7 +291,7 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
                         }
 #pragma unroll
                         for (int nt = 0; nt < 2; ++nt) {
-                            const float s16 = 16.f * bf16_bits_to_f32(cur.s[nt]);
+                            const float s16 = 16.f * bf16_bits_to_f32(ssc[(pi & 1) * 32 * G + (nt * 16 + c) * G + g]);
 #pragma unroll
                             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -253,10 +312,10 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
                         }
                     }
                     // refill this slot with the group R ahead
-                    fill(cur, r, nsrc, nssrc);
-                    // keep the groups apart in the schedule: hoisting the next group's LDS reads and
-                    // code expansion over this one only costs registers the ring needs
+                    fill(cur, r, nsrc);
+#ifdef QARL_SCHED_BARRIER
                     __builtin_amdgcn_sched_barrier(0);
+#endif
                 }
             }
             // ---- epilogue of this pair: lane (c,q) holds rows 4q..4q+3 of each token tile, column c
@@ -293,9 +352,8 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
                     }
                 }
             }
+            park_scales((pi + 1) & 1);
         }
-        // a further pass over the same tiles: restart the ring at this wavefront's first pair
-        if (m0 + kRowsMax * p.m_split < Me) fill_ring(0, 0);
     }
 }
 
@@ -303,8 +361,7 @@ template <int FMT, int EPI, int MT, int R>
 static int launch_cfg(const StreamParams &p, hipStream_t s)
 {
     constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
-    const int G = p.K / kGroup;
-    const size_t lds = (size_t)MT * 16 * 4 + (kInt4 ? (size_t)G * MT * 16 * 4 : 0) + (size_t)MT * 16 * x_stride(kInt4, p.K);
+    const size_t lds = stream_lds_bytes(kInt4, p.K, MT);
     if (lds > 160 * 1024) {
         set_error("qgemm (decode path): K=%d needs %zu bytes of LDS per workgroup, more than the 160 KiB of a CU", p.K, lds);
         return QARL_ERR_UNSUPPORTED;
@@ -327,9 +384,9 @@ template <int FMT, int EPI, int MT>
 static int launch_ring(const StreamParams &p, hipStream_t s)
 {
     const int G = p.K / kGroup;
-    // ring depth: the deepest that divides K/128 and still fits the register file beside the accumulators
-    if (MT <= 2 && G % 8 == 0) return launch_cfg<FMT, EPI, MT, 8>(p, s);
-    if (MT <= 2 && G % 6 == 0) return launch_cfg<FMT, EPI, MT, 6>(p, s);
+    // ring depth: the deepest that divides K/128
+    if (G % 8 == 0) return launch_cfg<FMT, EPI, MT, 8>(p, s);
+    if (G % 6 == 0) return launch_cfg<FMT, EPI, MT, 6>(p, s);
     if (G % 4 == 0) return launch_cfg<FMT, EPI, MT, 4>(p, s);
     if (G % 3 == 0) return launch_cfg<FMT, EPI, MT, 3>(p, s);
     if (G % 2 == 0) return launch_cfg<FMT, EPI, MT, 2>(p, s);
@@ -358,16 +415,15 @@ static int launch_one(const GemmArgs &a, hipStream_t s)
     const double mean = (double)a.M / (double)a.E;
     const double need = mean + 4.0 * sqrt(mean);
     // token tiles per workgroup: limited by the LDS tile, which holds the whole K of every row
-    const int row_bytes = x_stride(kInt4, a.K) + (kInt4 ? (a.K / kGroup) * 4 : 0) + 4;
-    const int mt_fit = (150 * 1024) / (16 * row_bytes);
+    const int mt_fit = stream_lds_bytes(kInt4, a.K, 2) <= 160 * 1024 ? 2 : (stream_lds_bytes(kInt4, a.K, 1) <= 160 * 1024 ? 1 : 0);
     if (mt_fit < 1) {
         set_error("qgemm (decode path): K=%d does not fit the LDS tile", a.K);
         return QARL_ERR_UNSUPPORTED;
     }
-    int MT = need <= 16.0 ? 1 : ((need <= 32.0 || mt_fit < 4) ? 2 : 4);
+    int MT = need <= 16.0 ? 1 : 2;  // more rows per expert go to further row blocks (m_split)
     if (MT > mt_fit) MT = 1;
     const int ms = (int)ceil(need / (16.0 * MT));
-    p.m_split = ms < 1 ? 1 : (ms > 4 ? 4 : ms);
+    p.m_split = ms < 1 ? 1 : (ms > 8 ? 8 : ms);
     // slices per expert: aim at one workgroup per CU, at least one pair of tiles per wavefront
     int slices = (256 + a.E * p.m_split - 1) / (a.E * p.m_split);
     const int max_slices = (p.n_units + kSWaves - 1) / kSWaves;
@@ -375,14 +431,22 @@ static int launch_one(const GemmArgs &a, hipStream_t s)
     if (slices < 1) slices = 1;
     p.n_slices = slices;
     if (MT == 1) return launch_ring<FMT, EPI, 1>(p, s);
-    if (MT == 2) return launch_ring<FMT, EPI, 2>(p, s);
-    return launch_ring<FMT, EPI, 4>(p, s);
+    return launch_ring<FMT, EPI, 2>(p, s);
+}
+
+bool qgemm_stream_supported(int fmt, int N, int K)
+{
+    if (N % 32 != 0) return false;
+    // int4: the per-pair scale fetch is sized for K/128 <= 16 groups and moves pairs of scales
+    if (fmt == QARL_W4A16_G128 && (K % 256 != 0 || K > 2048)) return false;
+    return stream_lds_bytes(fmt == QARL_W4A16_G128, K, 1) <= 160 * 1024;
 }
 
 int launch_qgemm_stream(const GemmArgs &a, hipStream_t s)
 {
-    if (a.N % 32 != 0) {
-        set_error("qgemm (decode path): N %% 32 == 0 required (got %d)", a.N);
+    if (!qgemm_stream_supported(a.fmt, a.N, a.K)) {
+        set_error("qgemm (decode path): unsupported shape N=%d K=%d (needs N %% 32 == 0; W4A16: K %% 256 == 0, K <= 2048; "
+                  "the token tile of one row block must fit LDS)", a.N, a.K);
         return QARL_ERR_UNSUPPORTED;
     }
     if (a.fmt == QARL_W4A16_G128)

@@ -35,16 +35,6 @@ struct TileParams {
     int total;      // n_blocks * m_slots rounded up to a multiple of 8
 };
 
-__device__ __forceinline__ bf16x8 unpack_int4_word_t(uint32_t w)
-{
-    u32x4 d;
-    d[0] = ((w << 3) & 0x00780078u) | 0x3f803f80u;
-    d[1] = ((w >> 1) & 0x00780078u) | 0x3f803f80u;
-    d[2] = ((w >> 5) & 0x00780078u) | 0x3f803f80u;
-    d[3] = ((w >> 9) & 0x00780078u) | 0x3f803f80u;
-    return __builtin_bit_cast(bf16x8, d);
-}
-
 template <int FMT, int EPI>
 __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
 {
@@ -116,9 +106,13 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
     tile_ok[0] = (EPI == QARL_EPI_SILU_MUL) ? (nrow[0] - c + 32 <= N / 2) : (nrow[0] - c + 32 <= N);
     tile_ok[1] = (EPI == QARL_EPI_SILU_MUL) ? tile_ok[0] : (nrow[1] - c + 32 <= N);
     const int words_per_row = kInt4 ? K / 8 : K / 4;
-    const uint32_t *wrow[2];
+    const uint32_t *wrow[2], *wblk[2];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) wrow[nt] = p.codes + ((int64_t)e * N + (tile_ok[nt] ? nrow[nt] : 0)) * words_per_row;
+    for (int nt = 0; nt < 2; ++nt) {
+        const int64_t r = (int64_t)e * N + (tile_ok[nt] ? nrow[nt] : 0);
+        wrow[nt] = p.codes + r * words_per_row;                      // fp8: row-major
+        wblk[nt] = p.codes + (r / 16) * G * 256 + (r % 16) * 4;      // int4: first block of the row's tile
+    }
 
     // ---- activation tile: 128 rows x 128 k, 16-byte blocks; 16 consecutive lanes cover one row
     constexpr int kBlkPerRow = kInt4 ? 16 : 8;
@@ -177,7 +171,10 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
             for (int u = 0; u < kWRegs; ++u) {
                 dst.w[nt][u] = u32x4{0, 0, 0, 0};
                 if (tile_ok[nt]) {
-                    const uint32_t *src = wrow[nt] + (kInt4 ? (g * 16 + h * 8 + u * 4) : (g * 32 + h * 16 + u * 4));
+                    // int4: block (16-row tile, group g) is 1 KiB; this lane's row is c & 15 of tile nrow/16 and
+                    // it takes the 16-byte pieces q = 2h + u (k in [32 q, +32)).  fp8: row-major bytes.
+                    const uint32_t *src = kInt4 ? wblk[nt] + ((int64_t)g * 64 + (2 * h + u) * 16) * 4
+                                                : wrow[nt] + (g * 32 + h * 16 + u * 4);
                     dst.w[nt][u] = *(const u32x4 *)src;
                 }
             }
@@ -222,8 +219,8 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
             }
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const bf16x8 b0 = unpack_int4_word_t(bcur.w[0][j >> 2][j & 3]);
-                const bf16x8 b1 = unpack_int4_word_t(bcur.w[1][j >> 2][j & 3]);
+                const bf16x8 b0 = unpack_int4_word(bcur.w[0][j >> 2][j & 3]);
+                const bf16x8 b1 = unpack_int4_word(bcur.w[1][j >> 2][j & 3]);
 #pragma unroll
                 for (int ms = 0; ms < 2; ++ms) {
                     const bf16x8 a =

@@ -1,5 +1,6 @@
 // Weight / activation quantizers: the Quant equations of section 2.2.
-//   int4: integer Quant with z = 0, one bf16 scale per 128 consecutive k of a row;
+//   int4: integer Quant with z = 0, one bf16 scale per 128 consecutive k of a row; codes are
+//         written in 1 KiB blocks of 16 rows x 128 k, the unit the GEMM kernels load;
 //   fp8 : FP Quant with alpha = 448 (e4m3), one fp32 scale per row.
 // Both are HBM-bound streams: 16-byte coalesced loads, the absmax reduced with
 // wavefront shuffles, IEEE fp32 divides so that codes and scales are reproducible
@@ -9,69 +10,73 @@
 namespace qarl {
 
 // ------------------------------------------------------------------ int4 --
-// A lane owns 8 consecutive k (one 16-byte load, one packed code word); 16 lanes
-// own a scale group; a wavefront covers 512 consecutive k = 1 KiB of the row-major
-// stream.  Each thread handles kUnroll such chunks, loads issued before use.
+// A wavefront produces one 1 KiB block of the packed layout: 16 rows x 128 k (one scale group of
+// each row).  Lane (c = lane & 15, q = lane >> 4) owns row c, k in [32 q, 32 q + 32): it reads 64
+// contiguous bytes of bf16, the four lanes of a row reduce the absmax with two shuffles, and the
+// lane writes its four code words as one 16-byte store at byte 16 * lane of the block.
 constexpr int kQThreads = 256;
-constexpr int kQUnroll = 4;
 
-__global__ __launch_bounds__(kQThreads) void quantize_int4_kernel(const u32x4 *__restrict__ w,
-                                                                  int64_t n_chunks,
-                                                                  uint32_t *__restrict__ codes,
+__global__ __launch_bounds__(kQThreads) void quantize_int4_kernel(const uint16_t *__restrict__ w, int64_t n_blocks,
+                                                                  int K, uint32_t *__restrict__ codes,
                                                                   uint16_t *__restrict__ scales)
 {
-    const int64_t base = ((int64_t)blockIdx.x * kQUnroll) * kQThreads + threadIdx.x;
-    u32x4 v[kQUnroll];
+    const int lane = threadIdx.x & 63;
+    const int c = lane & 15, q = lane >> 4;
+    const int G = K / kGroup;
+    const int64_t blk = (int64_t)blockIdx.x * (kQThreads / 64) + (threadIdx.x >> 6);
+    if (blk >= n_blocks) return;  // whole wavefront
+    const int64_t tile = blk / G;
+    const int g = (int)(blk % G);
+    const int64_t row = tile * 16 + c;
+    const u32x4 *src = (const u32x4 *)(w + row * K + g * kGroup + q * 32);
+    u32x4 v[4];
 #pragma unroll
-    for (int u = 0; u < kQUnroll; ++u) {
-        int64_t c = base + (int64_t)u * kQThreads;
-        v[u] = (c < n_chunks) ? __builtin_nontemporal_load(&w[c]) : u32x4{0, 0, 0, 0};
-    }
+    for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(&src[u]);
+    float f[32];
 #pragma unroll
-    for (int u = 0; u < kQUnroll; ++u) {
-        int64_t c = base + (int64_t)u * kQThreads;
-        float f[8];
+    for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            f[2 * i] = __uint_as_float(v[u][i] << 16);
-            f[2 * i + 1] = __uint_as_float(v[u][i] & 0xffff0000u);
+            f[u * 8 + 2 * i] = __uint_as_float(v[u][i] << 16);
+            f[u * 8 + 2 * i + 1] = __uint_as_float(v[u][i] & 0xffff0000u);
         }
-        float am = 0.f;
+    float am = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) am = fmaxf(am, fabsf(f[i]));
+    for (int i = 0; i < 32; ++i) am = fmaxf(am, fabsf(f[i]));
+    am = fmaxf(am, __shfl_xor(am, 16, 64));
+    am = fmaxf(am, __shfl_xor(am, 32, 64));
+    const uint32_t sb = f32_to_bf16_bits(am / 7.0f);
+    const float s = bf16_bits_to_f32(sb);
+    u32x4 out = {0x88888888u, 0x88888888u, 0x88888888u, 0x88888888u};  // code 0 everywhere
+    if (s != 0.f) {
 #pragma unroll
-        for (int o = 1; o < 16; o <<= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
-        const uint32_t sb = f32_to_bf16_bits(am / 7.0f);
-        const float s = bf16_bits_to_f32(sb);
-        uint32_t word = 0x88888888u;  // code 0 everywhere
-        if (s != 0.f) {
-            word = 0;
+        for (int u = 0; u < 4; ++u) {
+            uint32_t word = 0;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                float r = rintf(f[i] / s);
+                float r = rintf(f[u * 8 + i] / s);
                 r = fminf(fmaxf(r, -8.f), 7.f);
                 word |= (uint32_t)((int)r + 8) << (4 * i);
             }
-        }
-        if (c < n_chunks) {
-            __builtin_nontemporal_store(word, &codes[c]);
-            if ((c & 15) == 0) scales[c >> 4] = (uint16_t)sb;
+            out[u] = word;
         }
     }
+    __builtin_nontemporal_store(out, (u32x4 *)(codes + blk * 256 + lane * 4));
+    if (q == 0) scales[row * G + g] = (uint16_t)sb;
 }
 
 int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *scales, hipStream_t s)
 {
-    const int64_t n_chunks = rows * (int64_t)(K / 8);
-    if (n_chunks == 0) return QARL_OK;
-    const int64_t per_block = (int64_t)kQThreads * kQUnroll;
-    const int64_t blocks = (n_chunks + per_block - 1) / per_block;
-    if (blocks > 0x7fffffffLL) {
-        set_error("quantize: %lld blocks exceed the grid limit", (long long)blocks);
+    const int64_t n_blocks = (rows / 16) * (int64_t)(K / kGroup);
+    if (n_blocks == 0) return QARL_OK;
+    const int per_wg = kQThreads / 64;
+    const int64_t wgs = (n_blocks + per_wg - 1) / per_wg;
+    if (wgs > 0x7fffffffLL) {
+        set_error("quantize: %lld workgroups exceed the grid limit", (long long)wgs);
         return QARL_ERR_UNSUPPORTED;
     }
-    quantize_int4_kernel<<<dim3((unsigned)blocks), dim3(kQThreads), 0, s>>>(
-        (const u32x4 *)w, n_chunks, (uint32_t *)codes, (uint16_t *)scales);
+    quantize_int4_kernel<<<dim3((unsigned)wgs), dim3(kQThreads), 0, s>>>((const uint16_t *)w, n_blocks, K,
+                                                                         (uint32_t *)codes, (uint16_t *)scales);
     return check_hip(hipGetLastError(), "quantize_int4_kernel");
 }
 

@@ -60,3 +60,12 @@ def bf16_ulp_diff(a_bits, b_bits):
         x = x.astype(np.int32)
         return np.where(x & 0x8000, -(x & 0x7fff), x & 0x7fff)
     return np.abs(key(np.asarray(a_bits)) - key(np.asarray(b_bits)))
+
+
+def unblock_int4(codes, E, N, K):
+    """Packed W4A16 codes as the library stores them (1 KiB blocks of 16 rows x 128 k, see
+    include/qarl.h) -> the row-major word array [E, N, K/8] whose word j of a row holds elements
+    8j..8j+7.  Pure index permutation; the words themselves are untouched."""
+    w = np.ascontiguousarray(codes.detach().cpu().numpy()).view(np.uint32).reshape(E * N // 16, K // 128, 4, 16, 4)
+    # [tile, g, q, c, i] -> [tile, c, g, q, i]
+    return np.ascontiguousarray(w.transpose(0, 3, 1, 2, 4)).reshape(E, N, K // 8)

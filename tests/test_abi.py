@@ -26,12 +26,12 @@ def test_workspace_queries_and_host_side_validation():
     assert L.qarl_qgemm_workspace_bytes(q.QARL_EPI_NONE, 2048, 2048) == 0
     assert L.qarl_logprob_workspace_bytes(16384, 2048, 151936) == (2 * 594 + 1) * 16384 * 4
     # argument errors are reported before any launch, so they can be checked without a GPU
-    d = q.qarl_qweight(q.QARL_W4A16_G128, 1, 16, 100, 128, 16, 16)
+    d = q.qarl_qweight(q.QARL_W4A16_G128, 1, 32, 100, 128, 16, 16)
     assert L.qarl_quantize_weights(ctypes.c_void_p(16), ctypes.byref(d), None) == q.QARL_ERR_UNSUPPORTED
     assert b"K % 128" in L.qarl_last_error()
-    d = q.qarl_qweight(q.QARL_W4A16_G128, 1, 16, 128, 64, 16, 16)
+    d = q.qarl_qweight(q.QARL_W4A16_G128, 1, 32, 128, 64, 16, 16)
     assert L.qarl_quantize_weights(ctypes.c_void_p(16), ctypes.byref(d), None) == q.QARL_ERR_UNSUPPORTED
-    d = q.qarl_qweight(q.QARL_W4A16_G128, 1, 16, 128, 128, 8, 16)
+    d = q.qarl_qweight(q.QARL_W4A16_G128, 1, 32, 128, 128, 8, 16)
     assert L.qarl_quantize_weights(ctypes.c_void_p(16), ctypes.byref(d), None) == q.QARL_ERR_ALIGNMENT
     assert L.qarl_moe_route(None, 4, 100, 8, 1, None, None, None, None, None, None, None) == q.QARL_ERR_UNSUPPORTED
     assert L.qarl_moe_route(None, -1, 128, 8, 1, None, None, None, None, None, None, None) == q.QARL_ERR_INVALID_ARG

@@ -79,7 +79,7 @@ def test_one_hot_probe_bit_exact_both_paths(q, oracle, K, N):
 
 def test_exact_integer_regime_bit_exact(q, oracle):
     rng = np.random.default_rng(7)
-    E, N, K, M = 3, 64, 384, 75
+    E, N, K, M = 3, 64, 512, 75
     qi = rng.integers(-7, 8, size=(E, N, K))
     qi[:, :, ::128] = 7
     ex = rng.integers(-3, 2, size=(E, N, K // 128))

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from paper_2604_07853_amd import synth
-from gpu_util import np_bits
+from gpu_util import np_bits, unblock_int4
 
 pytestmark = pytest.mark.gpu
 
@@ -32,17 +32,17 @@ def _planted(w):
     return synth.from_bits(wb)
 
 
-@pytest.mark.parametrize("shape,seed", [((1, 768, 2048), 0), ((3, 48, 768), 1), ((2, 16, 128), 2)])
+@pytest.mark.parametrize("shape,seed", [((1, 768, 2048), 0), ((3, 64, 768), 1), ((2, 32, 128), 2)])
 def test_quantize_int4_bit_exact(q, oracle, shape, seed):
     w = _planted(synth.normal_bf16(shape, 0.02, seed))
     codes, scales = oracle.quantize_int4(np_bits(w))
     qw = q.qarl_quantize_weights(w.cuda(), q.QARL_W4A16_G128)
     torch.cuda.synchronize()
     assert np.array_equal(qw.scales.cpu().view(torch.int16).numpy().view(np.uint16), scales)
-    assert np.array_equal(qw.codes.cpu().numpy().view(np.uint32), codes)
+    assert np.array_equal(unblock_int4(qw.codes, *shape), codes)
 
 
-@pytest.mark.parametrize("shape,seed", [((2, 64, 2048), 3), ((1, 32, 768), 4), ((1, 16, 128), 5)])
+@pytest.mark.parametrize("shape,seed", [((2, 64, 2048), 3), ((1, 32, 768), 4), ((1, 32, 128), 5)])
 def test_quantize_fp8_bit_exact(q, oracle, shape, seed):
     w = _planted(synth.normal_bf16(shape, 0.02, seed))
     wb = np_bits(w).copy()
@@ -105,4 +105,4 @@ def test_route_empty_and_errors(q):
         q.qarl_moe_route(torch.zeros((4, 100), dtype=torch.bfloat16, device="cuda"), 8)
     assert ei.value.status == q.QARL_ERR_UNSUPPORTED
     with pytest.raises(q.QarlError):
-        q.qarl_quantize_weights(torch.zeros((1, 16, 100), dtype=torch.bfloat16, device="cuda"))
+        q.qarl_quantize_weights(torch.zeros((1, 32, 100), dtype=torch.bfloat16, device="cuda"))
