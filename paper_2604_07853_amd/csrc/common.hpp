@@ -65,6 +65,14 @@ __device__ __forceinline__ bf16x8 unpack_int4_word(uint32_t w)
     return __builtin_bit_cast(bf16x8, d);
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding
+// global load of the wavefront (the workgroup-scope fence waits on vmcnt), which would stall the
+// weight prefetch rings; kernels whose cross-wavefront traffic goes through LDS alone use this.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Host-side error plumbing (api.hip).
 void set_error(const char *fmt, ...);
 int check_hip(hipError_t e, const char *what);

@@ -55,7 +55,7 @@ __host__ __device__ constexpr int x_stride(bool int4, int K) { return K * (int4 
 static size_t stream_lds_bytes(bool int4, int K, int MT)
 {
     const size_t G = K / kGroup, rows = (size_t)MT * 16;
-    return rows * 4 + (int4 ? G * rows * 4 + (size_t)kSWaves * 2 * 32 * G * 2 : 0) + rows * x_stride(int4, K);
+    return rows * 4 + 16 + (int4 ? G * rows * 4 + (size_t)kSWaves * 2 * 32 * G * 2 : 0) + rows * x_stride(int4, K);
 }
 
 // FMT: weight format; EPI: NONE or SILU_MUL; MT: 16-row token tiles per block; R: ring depth in
@@ -82,20 +82,21 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
     const int e = unit_id / p.n_slices, slice = unit_id % p.n_slices;
 
     int *s_row = (int *)smem;                              // [kRowsMax]
-    float *sx = (float *)(smem + kRowsMax * 4);            // int4: [G][kRowsMax]  -1.5 * group sums
+    int *s_next = (int *)(smem + kRowsMax * 4);            // next undrawn pair
+    float *sx = (float *)(smem + kRowsMax * 4 + 16);       // int4: [G][kRowsMax]  -1.5 * group sums
     // int4: per wavefront two buffers of [2 tiles][16 rows][G] bf16 scales (this pair, next pair)
-    uint16_t *ssc = (uint16_t *)(smem + kRowsMax * 4 + (kInt4 ? G * kRowsMax * 4 : 0)) + (kInt4 ? wave * 2 * 32 * G : 0);
-    unsigned char *xs = smem + kRowsMax * 4 + (kInt4 ? G * kRowsMax * 4 + kSWaves * 2 * 32 * G * 2 : 0);  // [kRowsMax][stride]
+    uint16_t *ssc = (uint16_t *)(smem + kRowsMax * 4 + 16 + (kInt4 ? G * kRowsMax * 4 : 0)) + (kInt4 ? wave * 2 * 32 * G : 0);
+    unsigned char *xs = smem + kRowsMax * 4 + 16 + (kInt4 ? G * kRowsMax * 4 + kSWaves * 2 * 32 * G * 2 : 0);  // [kRowsMax][stride]
 
-    // this wavefront's pairs of weight tiles: units u_lo + wave, + 8, ...
+    // this workgroup's pairs of weight tiles: units u_lo .. u_hi-1
     const int per_slice = (p.n_units + p.n_slices - 1) / p.n_slices;
     const int u_lo = slice * per_slice, u_hi = min(p.n_units, u_lo + per_slice);
-    const int n_my = (u_hi - u_lo - wave + kSWaves - 1) / kSWaves;  // may be <= 0
+    const int n_pairs = max(0, u_hi - u_lo);  // pairs of this workgroup; wavefronts draw them from an LDS counter
     const int words_per_row = kInt4 ? K / 8 : K / 4;
     const int64_t ebase = (int64_t)e * N;
 
-    auto tile_row = [&](int pi, int nt) -> int {  // weight row of this lane in tile nt of its pi-th pair
-        const int u = u_lo + wave + pi * kSWaves;
+    auto tile_row = [&](int pi, int nt) -> int {  // weight row of this lane in tile nt of the slice's pi-th pair
+        const int u = u_lo + pi;
         if (EPI == QARL_EPI_SILU_MUL) return (nt ? N / 2 : 0) + u * 16 + c;
         return u * 32 + nt * 16 + c;
     };
@@ -110,13 +111,13 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
     // Past this wavefront's work the pointer falls back to the start of the expert's codes: the ring
     // is refilled without a branch (a conditional refill turns every slot into a merge of old and new
     // value and doubles the registers the ring takes), and those few loads all hit one cached line.
-    auto pair_tile16 = [&](int pi, int nt) -> int {  // index of the 16-row tile nt of this wavefront's pi-th pair
-        const int u = u_lo + wave + pi * kSWaves;
+    auto pair_tile16 = [&](int pi, int nt) -> int {  // index of the 16-row tile nt of the slice's pi-th pair
+        const int u = u_lo + pi;
         if (EPI == QARL_EPI_SILU_MUL) return (nt ? (N / 2) / 16 : 0) + u;
         return u * 2 + nt;
     };
     auto batch_src = [&](int pi, int g0, int nt) -> const uint32_t * {
-        const bool ok = pi < n_my;
+        const bool ok = pi < n_pairs;
         if (kInt4) {
             const int64_t tile = ebase / 16 + (ok ? pair_tile16(pi, nt) : 0);
             return p.codes + (tile * G + (ok ? g0 : 0)) * 256 + lane * 4;
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
             for (int u = 0; u < kScRegs; ++u) {
                 const int d = u * 64 + lane;
                 scr[u] = 0;
-                if (pi < n_my && d < 32 * half) {
+                if (pi < n_pairs && d < 32 * half) {
                     const int nt = d / (16 * half), rr = (d / half) % 16, dw = d % half;
                     const int64_t row = ebase + pair_tile16(pi, nt) * 16 + rr;
                     scr[u] = ((const uint32_t *)p.scales)[(row * G) / 2 + dw];
@@ -166,68 +167,59 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
         }
     };
 
-    // Start the weight stream at once: its addresses do not depend on the routing, and the first
-    // KiBs arrive while the row ids are looked up and the token tile is built.
-    load_scales(0);
-    fill_ring(0, 0);
-
     const int row0 = p.offsets[e];
     const int Me = p.offsets[e + 1] - row0;
     if (Me <= mh * kRowsMax) return;
 
-    bool first_pass = true;
     for (int m0 = mh * kRowsMax; m0 < Me; m0 += kRowsMax * p.m_split) {
         const int mrem = min(kRowsMax, Me - m0);
-        __syncthreads();  // previous pass is done with the LDS tile
-        if (!first_pass) {
-            load_scales(0);
-            fill_ring(0, 0);
-        }
-        first_pass = false;
+        lds_barrier();  // previous pass is done with the LDS tile
         if (tid < kRowsMax) {
             const int i = row0 + m0 + tid;
             s_row[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
         }
-        __syncthreads();
+        if (tid == 0) *s_next = kSWaves;  // pairs 0..7 start on wavefronts 0..7, the rest are drawn
+        lds_barrier();
         // ---- gather the token rows into LDS (whole K) in 16-byte blocks.  A thread keeps one block
-        // column and walks down the rows, so the only index arithmetic is an add per block.
+        // column and walks down the rows (at most kBatch of them: the workgroup sweeps >= 2 rows at a
+        // time), so the only index arithmetic is an add per block, and all its loads are in flight at
+        // once.  Vector loads return in order: the token rows are requested first and the weight
+        // stream right behind them, so it flows in while the tile is being built.
         {
             const int bpr = kInt4 ? K / 8 : K / 16;      // blocks per row
             const int rpp = kSThreads / bpr;             // rows covered per sweep of the workgroup
             const int rsub = tid / bpr, b = tid - rsub * bpr;
-            if (rsub < rpp) {
-                constexpr int kBatch = 8;
-                for (int rb = rsub; rb < kRowsMax; rb += rpp * kBatch) {
-                    u32x4 v[kBatch];
+            const bool active = rsub < rpp;
+            constexpr int kBatch = 16;
+            u32x4 v[kBatch];
 #pragma unroll
-                    for (int u = 0; u < kBatch; ++u) {
-                        const int r = rb + u * rpp;
-                        v[u] = u32x4{0, 0, 0, 0};
-                        if (r < kRowsMax) {
-                            const int xrow = s_row[r];
-                            if (xrow >= 0)
-                                v[u] = *(const u32x4 *)((const unsigned char *)p.x +
-                                                        (int64_t)xrow * K * (kInt4 ? 2 : 1) + b * 16);
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < kBatch; ++u) {
-                        const int r = rb + u * rpp;
-                        u32x4 o4 = v[u];
-                        if (kInt4) {
-                            // element order inside an 8-block follows the unpacked code order 0,4,1,5,2,6,3,7
-                            o4[0] = __builtin_amdgcn_perm(v[u][2], v[u][0], 0x05040100u);
-                            o4[1] = __builtin_amdgcn_perm(v[u][2], v[u][0], 0x07060302u);
-                            o4[2] = __builtin_amdgcn_perm(v[u][3], v[u][1], 0x05040100u);
-                            o4[3] = __builtin_amdgcn_perm(v[u][3], v[u][1], 0x07060302u);
-                        }
-                        if (r < kRowsMax) *(u32x4 *)(xs + r * stride + b * 16) = o4;
-                    }
+            for (int u = 0; u < kBatch; ++u) {
+                const int r = rsub + u * rpp;
+                v[u] = u32x4{0, 0, 0, 0};
+                if (active && r < kRowsMax) {
+                    const int xrow = s_row[r];
+                    if (xrow >= 0)
+                        v[u] = *(const u32x4 *)((const unsigned char *)p.x + (int64_t)xrow * K * (kInt4 ? 2 : 1) + b * 16);
                 }
+            }
+            load_scales(wave);
+            fill_ring(wave, 0);
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int r = rsub + u * rpp;
+                u32x4 o4 = v[u];
+                if (kInt4) {
+                    // element order inside an 8-block follows the unpacked code order 0,4,1,5,2,6,3,7
+                    o4[0] = __builtin_amdgcn_perm(v[u][2], v[u][0], 0x05040100u);
+                    o4[1] = __builtin_amdgcn_perm(v[u][2], v[u][0], 0x07060302u);
+                    o4[2] = __builtin_amdgcn_perm(v[u][3], v[u][1], 0x05040100u);
+                    o4[3] = __builtin_amdgcn_perm(v[u][3], v[u][1], 0x07060302u);
+                }
+                if (active && r < kRowsMax) *(u32x4 *)(xs + r * stride + b * 16) = o4;
             }
         }
         park_scales(0);
-        __syncthreads();
+        lds_barrier();
         if (kInt4) {
             // ---- group sums of the token rows, sx[g][m] = -1.5 * sum_k x[m][k], with the matrix core:
             // x times a matrix of ones; every column of the product holds the sums.
@@ -249,12 +241,18 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
                     }
                 }
             }
-            __syncthreads();
+            lds_barrier();
         }
 
         // ---- stream this wavefront's weight tiles
-        for (int pi = 0; pi < n_my; ++pi) {
-            load_scales(pi + 1);
+        // Wavefronts draw pairs from the LDS counter one pair ahead, so the two wavefronts that share a
+        // SIMD (one of which the arbiter favours) finish together instead of the slower one trailing.
+        int it = 0;
+        for (int pi = wave; pi < n_pairs; ++it) {
+            int npi = 0;
+            if (lane == 0) npi = atomicAdd(s_next, 1);
+            npi = __builtin_amdgcn_readfirstlane(npi);
+            load_scales(npi);
             f32x4 acc[2][MT];
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
@@ -263,8 +261,8 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
             for (int g0 = 0; g0 < G; g0 += R) {
                 // the batch that refills the ring while this one is consumed: same pair or the next one
                 const bool same = g0 + R < G;
-                const uint32_t *nsrc[2] = {batch_src(same ? pi : pi + 1, same ? g0 + R : 0, 0),
-                                           batch_src(same ? pi : pi + 1, same ? g0 + R : 0, 1)};
+                const uint32_t *nsrc[2] = {batch_src(same ? pi : npi, same ? g0 + R : 0, 0),
+                                           batch_src(same ? pi : npi, same ? g0 + R : 0, 1)};
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     const int g = g0 + r;
@@ -291,7 +289,7 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
                         }
 #pragma unroll
                         for (int nt = 0; nt < 2; ++nt) {
-                            const float s16 = 16.f * bf16_bits_to_f32(ssc[(pi & 1) * 32 * G + (nt * 16 + c) * G + g]);
+                            const float s16 = 16.f * bf16_bits_to_f32(ssc[(it & 1) * 32 * G + (nt * 16 + c) * G + g]);
 #pragma unroll
                             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -352,7 +350,8 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
                     }
                 }
             }
-            park_scales((pi + 1) & 1);
+            park_scales((it + 1) & 1);
+            pi = npi;
         }
     }
 }
@@ -384,9 +383,8 @@ template <int FMT, int EPI, int MT>
 static int launch_ring(const StreamParams &p, hipStream_t s)
 {
     const int G = p.K / kGroup;
-    // ring depth: the deepest that divides K/128
-    if (G % 8 == 0) return launch_cfg<FMT, EPI, MT, 8>(p, s);
-    if (G % 6 == 0) return launch_cfg<FMT, EPI, MT, 6>(p, s);
+    // ring depth (groups in flight per wavefront): four 1 KiB loads per tile already saturate HBM with eight
+    // wavefronts per CU, and a deeper ring would push the gather of the token rows into spilling
     if (G % 4 == 0) return launch_cfg<FMT, EPI, MT, 4>(p, s);
     if (G % 3 == 0) return launch_cfg<FMT, EPI, MT, 3>(p, s);
     if (G % 2 == 0) return launch_cfg<FMT, EPI, MT, 2>(p, s);
@@ -439,6 +437,7 @@ bool qgemm_stream_supported(int fmt, int N, int K)
     if (N % 32 != 0) return false;
     // int4: the per-pair scale fetch is sized for K/128 <= 16 groups and moves pairs of scales
     if (fmt == QARL_W4A16_G128 && (K % 256 != 0 || K > 2048)) return false;
+    if (fmt == QARL_FP8_E4M3_CH && K > 4096) return false;  // the gather sweeps >= 2 rows per step
     return stream_lds_bytes(fmt == QARL_W4A16_G128, K, 1) <= 160 * 1024;
 }
 
