@@ -104,7 +104,7 @@ def main():
             a, b = ev(), ev()
             a.record()
         q.qarl_qgemm_grouped(layer.gu, x, r.offsets, M, row_map=r.tokens, epilogue=q.QARL_EPI_SILU_MUL,
-                             out=layer.a, path=q.QARL_PATH_DECODE)
+                             out=layer.a, path=q.QARL_PATH_DECODE, ws=layer.ws)
         if record:
             b.record()
             gu_events.append((a, b))
@@ -204,9 +204,12 @@ def main():
         Mp = Tp * TOPK
         ms_gu_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.gu, xp, r.offsets, Mp, row_map=r.tokens,
                                                      epilogue=q.QARL_EPI_SILU_MUL, out=lp_layer.a,
-                                                     path=q.QARL_PATH_PREFILL), 10, 2)
-        ms_dn_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.dn, lp_layer.a, r.offsets, Mp, out=lp_layer.ws.view(torch.float32)[:Mp * H].view(Mp, H),
-                                                     out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_PREFILL), 10, 2)
+                                                     path=q.QARL_PATH_PREFILL, ws=lp_layer.ws), 10, 2)
+        ybuf = torch.empty((Mp, H), dtype=torch.float32, device=dev)
+        ms_dn_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.dn, lp_layer.a, r.offsets, Mp, out=ybuf,
+                                                     out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_PREFILL,
+                                                     ws=lp_layer.ws), 10, 2)
+        del ybuf
         fl_gu, fl_dn = 2 * Mp * 2 * I * H, 2 * Mp * H * I
         extra["prefill_w4a16_16384tok_zipf"] = {
             "layer_ms": round(ms_all, 4), "gate_up_ms": round(ms_gu_p, 4), "down_ms": round(ms_dn_p, 4),

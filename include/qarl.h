@@ -74,9 +74,11 @@ typedef struct {
 
 const char *qarl_last_error(void);
 
-/* Bytes of `ws` that qarl_qgemm_grouped needs for the given call (0 unless the epilogue is
- * COMBINE, which stages Y in fp32), and that qarl_token_logprob needs. */
-size_t qarl_qgemm_workspace_bytes(int epilogue, int64_t M, int N);
+/* Bytes of `ws` that qarl_qgemm_grouped may need for a call with these weights, x_rows activation
+ * rows, M problem rows and this epilogue, whichever path runs: fp32 staging of Y [M][N] for COMBINE,
+ * plus, for W4A16, one fp32 sum per activation row and 128-k scale group (the prefill path computes
+ * them once per call).  qarl_token_logprob has its own query. */
+size_t qarl_qgemm_workspace_bytes(const qarl_qweight *W, int64_t x_rows, int64_t M, int epilogue);
 size_t qarl_logprob_workspace_bytes(int T, int H, int V);
 
 /* Quant of section 2.2 applied to bf16 master weights w [E][N][K], the on-the-fly
@@ -123,7 +125,7 @@ int qarl_moe_route(const void *logits_bf16, int T, int E, int topk, int renorm, 
  *   path       AUTO picks DECODE when the mean rows per expert is small and the shape fits it
  *              (DECODE keeps whole rows of x in LDS: W4A16 needs K % 256 == 0 and K <= 2048)
  * Errors: INVALID_ARG, ALIGNMENT, UNSUPPORTED (shape outside the kernels' domain),
- * WORKSPACE (ws too small).  M == 0 is a no-op (COMBINE still zero-fills out). */
+ * WORKSPACE (ws missing or smaller than the call needs).  M == 0 is a no-op. */
 int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scales, int64_t x_rows,
                        const int32_t *row_map, const int32_t *expert_offsets, int64_t M,
                        int epilogue, const float *combine_w, const int32_t *sorted_pairs, int T,

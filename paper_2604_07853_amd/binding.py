@@ -49,7 +49,7 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.qarl_last_error.restype = C.c_char_p
         L.qarl_qgemm_workspace_bytes.restype = C.c_size_t
-        L.qarl_qgemm_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int]
+        L.qarl_qgemm_workspace_bytes.argtypes = [C.POINTER(qarl_qweight), C.c_int64, C.c_int64, C.c_int]
         L.qarl_logprob_workspace_bytes.restype = C.c_size_t
         L.qarl_logprob_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
         L.qarl_quantize_weights.argtypes = [C.c_void_p, C.POINTER(qarl_qweight), C.c_void_p]
@@ -147,8 +147,8 @@ def qarl_moe_route(logits, topk=8, renorm=True, out=None):
     return r
 
 
-def qarl_qgemm_workspace_bytes(epilogue, M, N):
-    return lib().qarl_qgemm_workspace_bytes(epilogue, M, N)
+def qarl_qgemm_workspace_bytes(W, x_rows, M, epilogue):
+    return lib().qarl_qgemm_workspace_bytes(C.byref(W.desc), x_rows, M, epilogue)
 
 
 def qarl_qgemm_grouped(W, x, expert_offsets, M, row_map=None, x_scales=None, epilogue=QARL_EPI_NONE,
@@ -165,7 +165,7 @@ def qarl_qgemm_grouped(W, x, expert_offsets, M, row_map=None, x_scales=None, epi
             out = torch.empty((M, N // 2), dtype=dt, device=dev)
         else:
             out = torch.empty((M, N), dtype=dt, device=dev)
-    need = lib().qarl_qgemm_workspace_bytes(epilogue, M, N)
+    need = qarl_qgemm_workspace_bytes(W, x.shape[0], M, epilogue)
     if ws is None and need:
         ws = torch.empty((need,), dtype=torch.uint8, device=dev)
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
@@ -226,8 +226,9 @@ class MoELayer:
         self.routing = Routing(T, E, topk, device)
         self.a = torch.empty((M, I), dtype=torch.bfloat16, device=device)
         self.out = torch.empty((T, H), dtype=torch.bfloat16, device=device)
-        self.ws = torch.empty((max(lib().qarl_qgemm_workspace_bytes(QARL_EPI_COMBINE, M, H), 16),),
-                              dtype=torch.uint8, device=device)
+        need = max(qarl_qgemm_workspace_bytes(gate_up, T, M, QARL_EPI_SILU_MUL),
+                   qarl_qgemm_workspace_bytes(down, M, M, QARL_EPI_COMBINE), 16)
+        self.ws = torch.empty((need,), dtype=torch.uint8, device=device)
         if self.fp8:
             self.xq = torch.empty((T, H), dtype=torch.uint8, device=device)
             self.sx = torch.empty((T,), dtype=torch.float32, device=device)
@@ -246,7 +247,7 @@ class MoELayer:
                                path=self.path, ws=self.ws)
         else:
             qarl_qgemm_grouped(self.gu, x, r.offsets, self.M, row_map=r.tokens, epilogue=QARL_EPI_SILU_MUL,
-                               out=self.a, path=self.path)
+                               out=self.a, path=self.path, ws=self.ws)
             qarl_qgemm_grouped(self.dn, self.a, r.offsets, self.M, epilogue=QARL_EPI_COMBINE, combine_w=r.w,
                                sorted_pairs=r.pairs, T=self.T, topk=self.topk, out=self.out, path=self.path,
                                ws=self.ws)

@@ -66,10 +66,22 @@ extern "C" {
 
 const char *qarl_last_error(void) { return g_err; }
 
-size_t qarl_qgemm_workspace_bytes(int epilogue, int64_t M, int N)
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+static size_t ws_stage_bytes(const qarl_qweight *W, int64_t M, int epilogue)
 {
-    if (epilogue != QARL_EPI_COMBINE || M <= 0 || N <= 0) return 0;
-    return (size_t)M * (size_t)N * sizeof(float);
+    return epilogue == QARL_EPI_COMBINE ? align256((size_t)M * (size_t)W->N * sizeof(float)) : 0;
+}
+
+static size_t ws_sums_bytes(const qarl_qweight *W, int64_t x_rows)
+{
+    return W->fmt == QARL_W4A16_G128 ? align256((size_t)x_rows * (size_t)(W->K / 128) * sizeof(float)) : 0;
+}
+
+size_t qarl_qgemm_workspace_bytes(const qarl_qweight *W, int64_t x_rows, int64_t M, int epilogue)
+{
+    if (!W || M <= 0 || x_rows <= 0 || W->N <= 0 || W->K <= 0) return 0;
+    return ws_stage_bytes(W, M, epilogue) + ws_sums_bytes(W, x_rows);
 }
 
 size_t qarl_logprob_workspace_bytes(int T, int H, int V)
@@ -213,24 +225,32 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
     a.epilogue = epilogue;
     a.out = out;
     a.out_f32 = (out_dtype == QARL_OUT_F32);
+    a.x_group_sums = nullptr;
+    int use = path;
+    if (use == QARL_PATH_AUTO)
+        use = (M <= (int64_t)W->E * 64 && qgemm_stream_supported(W->fmt, W->N, W->K)) ? QARL_PATH_DECODE : QARL_PATH_PREFILL;
+    const size_t stage = ws_stage_bytes(W, M, epilogue);
+    const size_t sums = (use == QARL_PATH_PREFILL) ? ws_sums_bytes(W, x_rows) : 0;
+    if (stage + sums > 0 && (!ws || ws_bytes < stage + sums || !aligned16(ws))) {
+        set_error("qarl_qgemm_grouped: this call needs %zu bytes of 16-byte aligned workspace (got %zu)", stage + sums, ws_bytes);
+        return QARL_ERR_WORKSPACE;
+    }
     if (epilogue == QARL_EPI_COMBINE) {
         if (!combine_w || !sorted_pairs) {
             set_error("qarl_qgemm_grouped: COMBINE needs combine_w and sorted_pairs");
             return QARL_ERR_INVALID_ARG;
-        }
-        const size_t need = qarl_qgemm_workspace_bytes(epilogue, M, W->N);
-        if (!ws || ws_bytes < need || !aligned16(ws)) {
-            set_error("qarl_qgemm_grouped: COMBINE needs %zu bytes of 16-byte aligned workspace (got %zu)", need, ws_bytes);
-            return QARL_ERR_WORKSPACE;
         }
         a.epilogue = QARL_EPI_NONE;
         a.out = ws;
         a.out_f32 = 1;
         a.out_row_map = sorted_pairs;  // Y lands in pair order: row t*topk + slot
     }
-    int use = path;
-    if (use == QARL_PATH_AUTO)
-        use = (M <= (int64_t)W->E * 64 && qgemm_stream_supported(W->fmt, W->N, W->K)) ? QARL_PATH_DECODE : QARL_PATH_PREFILL;
+    if (sums) {
+        float *gs = (float *)((char *)ws + stage);
+        rc = launch_group_sums(x, x_rows, W->K, gs, st);
+        if (rc) return rc;
+        a.x_group_sums = gs;
+    }
     rc = (use == QARL_PATH_DECODE) ? launch_qgemm_stream(a, st) : launch_qgemm_tile(a, st);
     if (rc) return rc;
     if (epilogue == QARL_EPI_COMBINE)

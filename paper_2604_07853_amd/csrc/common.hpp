@@ -90,6 +90,7 @@ struct GemmArgs {
     const void *scales;
     const void *x;
     const float *x_scales;
+    const float *x_group_sums;   // W4A16 prefill path: -1.5 * sum of x over each 128-k group, [x_rows][K/128]
     const int32_t *row_map;      // gather of activation rows, or null
     const int32_t *out_row_map;  // scatter of output rows, or null
     const int32_t *offsets;
@@ -101,6 +102,7 @@ struct GemmArgs {
 int launch_qgemm_stream(const GemmArgs &a, hipStream_t s);
 bool qgemm_stream_supported(int fmt, int N, int K);
 int launch_qgemm_tile(const GemmArgs &a, hipStream_t s);
+int launch_group_sums(const void *x_bf16, int64_t rows, int K, float *sums, hipStream_t s);
 int launch_combine(const float *y_pair_order, const float *w, int T, int topk, int N, void *out, int out_f32,
                    hipStream_t s);
 int launch_logprob(const void *h, const void *wlm, const int32_t *target, int T, int H, int V,

@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kLThreads, 1) void lmhead_lse_kernel(LogprobParams 
     load_a(0);
     load_b(bcur, 0);
     store_a(0);
-    __syncthreads();
+    lds_barrier();
     for (int ks = 0; ks < steps; ++ks) {
         if (ks + 1 < steps) {
             load_a(ks + 1);
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kLThreads, 1) void lmhead_lse_kernel(LogprobParams 
             store_a((ks + 1) & 1);
             bcur = bnxt;
         }
-        __syncthreads();
+        lds_barrier();
     }
 
     // ---- per-row (max, sum exp) over this workgroup's 256 columns, and the target logit
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kLThreads, 1) void lmhead_lse_kernel(LogprobParams 
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
     if (tid < kLBM && row0 + tid < T) {
         float m = fmaxf(fmaxf(s_m[0][tid], s_m[1][tid]), fmaxf(s_m[2][tid], s_m[3][tid]));
         float s = 0.f;

@@ -9,7 +9,8 @@
 // packed weights go global -> registers and are expanded there, so the LDS only carries the
 // activation operand.  W4A16 group handling is the one described in qgemm_stream.hip: codes
 // become the exact bf16 values (q+24)/16, every scale group accumulates in its own fp32
-// accumulator that starts at -1.5 * sum_k x, and is folded in with one FMA by 16*s.
+// accumulator that starts at -1.5 * sum_k x (the sums come from a small pre-pass over the
+// activations, once per call), and is folded in with one FMA by 16*s.
 #include "common.hpp"
 
 namespace qarl {
@@ -25,6 +26,7 @@ struct TileParams {
     const void *scales;
     const void *x;
     const float *x_scales;
+    const float *x_group_sums;
     const int32_t *row_map;
     const int32_t *out_row_map;
     const int32_t *offsets;
@@ -65,13 +67,13 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
         s_scan[tid] = t;
     }
     if (tid == 0) s_expert = -1;
-    __syncthreads();
+    lds_barrier();
     for (int o = 1; o < 256; o <<= 1) {
         int add = 0;
         if (tid < 256 && tid >= o) add = s_scan[tid - o];
-        __syncthreads();
+        lds_barrier();
         if (tid < 256) s_scan[tid] += add;
-        __syncthreads();
+        lds_barrier();
     }
     if (tid < p.E) {
         const int incl = s_scan[tid];
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
             s_mtile = slot - excl;
         }
     }
-    __syncthreads();
+    lds_barrier();
     const int e = s_expert;
     if (e < 0) return;
     const int row0 = p.offsets[e] + s_mtile * kBM;
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
         const int i = row0 + tid;
         s_rows[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
     }
-    __syncthreads();
+    lds_barrier();
 
     const int N = p.N, K = p.K, G = K / kGroup;
     // weight rows of this lane's two column tiles
@@ -118,7 +120,12 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
     constexpr int kBlkPerRow = kInt4 ? 16 : 8;
     constexpr int kARegs = kBM * kBlkPerRow / kTThreads;  // 4 or 2
     u32x4 ar[kARegs];
+    float gsum = 0.f;  // W4A16: -1.5 * sum of this thread's row over the group (threads < kBM)
     auto load_a = [&](int g) {
+        if (kInt4 && tid < kBM) {
+            const int xrow = s_rows[tid];
+            gsum = xrow >= 0 ? p.x_group_sums[(int64_t)xrow * (K / kGroup) + g] : 0.f;
+        }
 #pragma unroll
         for (int u = 0; u < kARegs; ++u) {
             const int idx = u * kTThreads + tid;
@@ -135,24 +142,18 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
     auto store_a = [&](int buf) {
         unsigned char *xs = smem + buf * kBufBytes;
         float *sx = (float *)(xs + kBM * kStride);
+        if (kInt4 && tid < kBM) sx[tid] = gsum;
 #pragma unroll
         for (int u = 0; u < kARegs; ++u) {
             const int idx = u * kTThreads + tid;
             const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
             u32x4 v4 = ar[u];
             if (kInt4) {
-                float sum = 0.f;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sum += __uint_as_float(v4[i] << 16) + __uint_as_float(v4[i] & 0xffff0000u);
-#pragma unroll
-                for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
-                if (b == 0) sx[r] = -1.5f * sum;
-                u32x4 o4;  // element order 0,4,1,5,2,6,3,7 inside every 8-block (the unpacked code order)
-                o4[0] = (v4[0] & 0xffffu) | (v4[2] << 16);
-                o4[1] = (v4[0] >> 16) | (v4[2] & 0xffff0000u);
-                o4[2] = (v4[1] & 0xffffu) | (v4[3] << 16);
-                o4[3] = (v4[1] >> 16) | (v4[3] & 0xffff0000u);
-                v4 = o4;
+                // element order 0,4,1,5,2,6,3,7 inside every 8-block (the unpacked code order)
+                v4[0] = __builtin_amdgcn_perm(ar[u][2], ar[u][0], 0x05040100u);
+                v4[1] = __builtin_amdgcn_perm(ar[u][2], ar[u][0], 0x07060302u);
+                v4[2] = __builtin_amdgcn_perm(ar[u][3], ar[u][1], 0x05040100u);
+                v4[3] = __builtin_amdgcn_perm(ar[u][3], ar[u][1], 0x07060302u);
             }
             *(u32x4 *)(xs + r * kStride + b * 16) = v4;
         }
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
     load_a(0);
     load_b(bcur, 0);
     store_a(0);
-    __syncthreads();
+    lds_barrier();
     for (int g = 0; g < G; ++g) {
         if (g + 1 < G) {
             load_a(g + 1);
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
             store_a((g + 1) & 1);
             bcur = bnxt;
         }
-        __syncthreads();
+        lds_barrier();
     }
 
     // ---- epilogue: lane (c,h), register i -> token row 8*(i/4) + 4h + i%4, column c of each tile
@@ -312,6 +313,7 @@ static int launch_one(const GemmArgs &a, hipStream_t s)
     p.scales = a.scales;
     p.x = a.x;
     p.x_scales = a.x_scales;
+    p.x_group_sums = a.x_group_sums;
     p.row_map = a.row_map;
     p.out_row_map = a.out_row_map;
     p.offsets = a.offsets;
@@ -341,6 +343,35 @@ static int launch_one(const GemmArgs &a, hipStream_t s)
     }
     kern<<<dim3((unsigned)total), dim3(kTThreads), lds, s>>>(p);
     return check_hip(hipGetLastError(), "qgemm_tile_kernel");
+}
+
+// sums[row][g] = -1.5 * sum over the 128 k of group g of x[row][k]: the start value of a group's
+// accumulator (it cancels the +24/16 offset of the expanded codes).  16 lanes own a group.
+__global__ __launch_bounds__(256) void group_sums_kernel(const u32x4 *__restrict__ x, int64_t n_chunks,
+                                                         float *__restrict__ sums)
+{
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;  // 16-byte chunk = 8 elements
+    u32x4 v = {0, 0, 0, 0};
+    if (c < n_chunks) v = x[c];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s += __uint_as_float(v[i] << 16) + __uint_as_float(v[i] & 0xffff0000u);
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o, 64);
+    if (c < n_chunks && (c & 15) == 0) sums[c >> 4] = -1.5f * s;
+}
+
+int launch_group_sums(const void *x_bf16, int64_t rows, int K, float *sums, hipStream_t s)
+{
+    const int64_t n_chunks = rows * (int64_t)(K / 8);
+    if (n_chunks == 0) return QARL_OK;
+    const int64_t blocks = (n_chunks + 255) / 256;
+    if (blocks > 0x7fffffffLL) {
+        set_error("group sums: grid too large");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    group_sums_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x4 *)x_bf16, n_chunks, sums);
+    return check_hip(hipGetLastError(), "group_sums_kernel");
 }
 
 int launch_qgemm_tile(const GemmArgs &a, hipStream_t s)

@@ -22,8 +22,13 @@ def test_library_exports_all_declared_symbols():
 def test_workspace_queries_and_host_side_validation():
     from paper_2604_07853_amd import binding as q
     L = q.lib()
-    assert L.qarl_qgemm_workspace_bytes(q.QARL_EPI_COMBINE, 2048, 2048) == 2048 * 2048 * 4
-    assert L.qarl_qgemm_workspace_bytes(q.QARL_EPI_NONE, 2048, 2048) == 0
+    d4 = q.qarl_qweight(q.QARL_W4A16_G128, 128, 2048, 768, 128, 16, 16)
+    d8 = q.qarl_qweight(q.QARL_FP8_E4M3_CH, 128, 2048, 768, 0, 16, 16)
+    by = ctypes.byref
+    assert L.qarl_qgemm_workspace_bytes(by(d8), 2048, 2048, q.QARL_EPI_COMBINE) == 2048 * 2048 * 4
+    assert L.qarl_qgemm_workspace_bytes(by(d8), 2048, 2048, q.QARL_EPI_NONE) == 0
+    assert L.qarl_qgemm_workspace_bytes(by(d4), 2048, 2048, q.QARL_EPI_NONE) == 2048 * 6 * 4
+    assert L.qarl_qgemm_workspace_bytes(by(d4), 2048, 2048, q.QARL_EPI_COMBINE) == 2048 * 2048 * 4 + 2048 * 6 * 4
     assert L.qarl_logprob_workspace_bytes(16384, 2048, 151936) == (2 * 594 + 1) * 16384 * 4
     # argument errors are reported before any launch, so they can be checked without a GPU
     d = q.qarl_qweight(q.QARL_W4A16_G128, 1, 32, 100, 128, 16, 16)
