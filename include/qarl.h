@@ -59,7 +59,9 @@ typedef enum { QARL_OUT_BF16 = 0, QARL_OUT_F32 = 1 } qarl_out_dtype;
  *   W4A16_G128: codes  uint32, E*N*K/8 words in 1 KiB blocks of 16 rows x 128 k (one scale group
  *                      of 16 consecutive rows), the unit a wavefront of the GEMM kernels loads:
  *                      [E*N/16 row tiles][K/128 groups][4 (k%128)/32][16 n%16][4 (k%32)/8] words;
- *                      element k%8 = i of a word sits in its bits [4i,4i+3] as q+8, q in [-8,7];
+ *                      a word holds 8 consecutive k as nibbles q+8, q in [-8,7]: element k%8 = 2i+b sits
+ *                      in nibble i+4b (bits [4(i+4b), 4(i+4b)+3]), so the nibble pair (i, i+4) that one
+ *                      shift-and-mask extracts is the pair of neighbours (2i, 2i+1);
  *               scales bf16   [E][N][K/128]; dequantized weight = float(scale) * q, exact in
  *                      fp32 and never rounded to 16 bits.
  *   FP8_E4M3_CH: codes uint8  [E][N][K] (e4m3 bit patterns); scales float [E][N].

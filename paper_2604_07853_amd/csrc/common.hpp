@@ -51,9 +51,10 @@ __device__ __forceinline__ uint32_t and_or_b32(uint32_t a, uint32_t mask, uint32
     return d;
 }
 
-// One packed word of eight int4 codes (element i in bits [4i,4i+3], stored as q+8) -> eight exact
-// bf16 values (q+24)/16 in the order c0,c4,c1,c5,c2,c6,c3,c7: the nibble lands in the top four
-// mantissa bits of bf16 1.0.  One shift and one and-or per pair of codes.
+// One packed word of eight int4 codes (element 2i+b in nibble i+4b, stored as q+8) -> eight exact
+// bf16 values (q+24)/16 in element order 0..7: the nibble lands in the top four mantissa bits of
+// bf16 1.0, and nibbles i and i+4 fall into the two halves of output dword i.  One shift and one
+// and-or per pair of codes.
 __device__ __forceinline__ bf16x8 unpack_int4_word(uint32_t w)
 {
     const uint32_t mask = 0x00780078u, one = 0x3f803f80u;

@@ -207,14 +207,7 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 const int r = rsub + u * rpp;
-                u32x4 o4 = v[u];
-                if (kInt4) {
-                    // element order inside an 8-block follows the unpacked code order 0,4,1,5,2,6,3,7
-                    o4[0] = __builtin_amdgcn_perm(v[u][2], v[u][0], 0x05040100u);
-                    o4[1] = __builtin_amdgcn_perm(v[u][2], v[u][0], 0x07060302u);
-                    o4[2] = __builtin_amdgcn_perm(v[u][3], v[u][1], 0x05040100u);
-                    o4[3] = __builtin_amdgcn_perm(v[u][3], v[u][1], 0x07060302u);
-                }
+                const u32x4 o4 = v[u];
                 if (active && r < kRowsMax) *(u32x4 *)(xs + r * stride + b * 16) = o4;
             }
         }

@@ -147,14 +147,7 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
         for (int u = 0; u < kARegs; ++u) {
             const int idx = u * kTThreads + tid;
             const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
-            u32x4 v4 = ar[u];
-            if (kInt4) {
-                // element order 0,4,1,5,2,6,3,7 inside every 8-block (the unpacked code order)
-                v4[0] = __builtin_amdgcn_perm(ar[u][2], ar[u][0], 0x05040100u);
-                v4[1] = __builtin_amdgcn_perm(ar[u][2], ar[u][0], 0x07060302u);
-                v4[2] = __builtin_amdgcn_perm(ar[u][3], ar[u][1], 0x05040100u);
-                v4[3] = __builtin_amdgcn_perm(ar[u][3], ar[u][1], 0x07060302u);
-            }
+            const u32x4 v4 = ar[u];
             *(u32x4 *)(xs + r * kStride + b * 16) = v4;
         }
     };
@@ -218,16 +211,44 @@ __global__ __launch_bounds__(kTThreads, 1) void qgemm_tile_kernel(TileParams p)
                     }
                 }
             }
+            // Software pipeline over the eight 16-k slices: the LDS reads and the code expansion of
+            // slice j+1 are issued under the four MFMAs of slice j; the group barriers pin that
+            // interleaving (MFMA, two LDS reads, VALU, MFMA, VALU, ...) in the machine schedule.
+            bf16x8 a_c[2], b_c[2];
+#pragma unroll
+            for (int ms = 0; ms < 2; ++ms)
+                a_c[ms] = *(const bf16x8 *)(xs + (wm * 64 + ms * 32 + c) * kStride + (h * 64) * 2);
+            b_c[0] = unpack_int4_word(bcur.w[0][0][0]);
+            b_c[1] = unpack_int4_word(bcur.w[1][0][0]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const bf16x8 b0 = unpack_int4_word(bcur.w[0][j >> 2][j & 3]);
-                const bf16x8 b1 = unpack_int4_word(bcur.w[1][j >> 2][j & 3]);
+                bf16x8 a_n[2], b_n[2];
+                if (j < 7) {
+#pragma unroll
+                    for (int ms = 0; ms < 2; ++ms)
+                        a_n[ms] = *(const bf16x8 *)(xs + (wm * 64 + ms * 32 + c) * kStride + (h * 64 + (j + 1) * 8) * 2);
+                    b_n[0] = unpack_int4_word(bcur.w[0][(j + 1) >> 2][(j + 1) & 3]);
+                    b_n[1] = unpack_int4_word(bcur.w[1][(j + 1) >> 2][(j + 1) & 3]);
+                }
 #pragma unroll
                 for (int ms = 0; ms < 2; ++ms) {
-                    const bf16x8 a =
-                        *(const bf16x8 *)(xs + (wm * 64 + ms * 32 + c) * kStride + (h * 64 + j * 8) * 2);
-                    ag[ms][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, ag[ms][0], 0, 0, 0);
-                    ag[ms][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, ag[ms][1], 0, 0, 0);
+                    ag[ms][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_c[ms], b_c[0], ag[ms][0], 0, 0, 0);
+                    ag[ms][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_c[ms], b_c[1], ag[ms][1], 0, 0, 0);
+                }
+                if (j < 7) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // the two LDS reads of slice j+1
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // VALU: code expansion
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+#pragma unroll
+                    for (int ms = 0; ms < 2; ++ms) a_c[ms] = a_n[ms];
+                    b_c[0] = b_n[0];
+                    b_c[1] = b_n[1];
                 }
             }
 #pragma unroll

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kQThreads) void quantize_int4_kernel(const uint16_t
             for (int i = 0; i < 8; ++i) {
                 float r = rintf(f[u * 8 + i] / s);
                 r = fminf(fmaxf(r, -8.f), 7.f);
-                word |= (uint32_t)((int)r + 8) << (4 * i);
+                word |= (uint32_t)((int)r + 8) << (4 * ((i >> 1) + 4 * (i & 1)));  // element 2j+b -> nibble j+4b
             }
             out[u] = word;
         }

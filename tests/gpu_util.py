@@ -63,9 +63,14 @@ def bf16_ulp_diff(a_bits, b_bits):
 
 
 def unblock_int4(codes, E, N, K):
-    """Packed W4A16 codes as the library stores them (1 KiB blocks of 16 rows x 128 k, see
-    include/qarl.h) -> the row-major word array [E, N, K/8] whose word j of a row holds elements
-    8j..8j+7.  Pure index permutation; the words themselves are untouched."""
+    """Packed W4A16 codes as the library stores them (1 KiB blocks of 16 rows x 128 k, element 2i+b
+    of a word in nibble i+4b; see include/qarl.h) -> the oracle's packing: row-major words [E, N, K/8],
+    element i of a word in nibble i.  Pure index permutation of words and nibbles."""
     w = np.ascontiguousarray(codes.detach().cpu().numpy()).view(np.uint32).reshape(E * N // 16, K // 128, 4, 16, 4)
     # [tile, g, q, c, i] -> [tile, c, g, q, i]
-    return np.ascontiguousarray(w.transpose(0, 3, 1, 2, 4)).reshape(E, N, K // 8)
+    w = np.ascontiguousarray(w.transpose(0, 3, 1, 2, 4)).reshape(E, N, K // 8)
+    out = np.zeros_like(w)
+    for el in range(8):
+        nib = (el >> 1) + 4 * (el & 1)
+        out |= ((w >> np.uint32(4 * nib)) & np.uint32(15)) << np.uint32(4 * el)
+    return out
