@@ -13,6 +13,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 constexpr int kWave = 64;
 constexpr int kGroup = 128;  // k per int4 scale group
@@ -26,6 +27,20 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
     u += 0x7fffu + ((u >> 16) & 1u);
     return u >> 16;
+}
+
+// The same conversion by the hardware instruction (round-to-nearest-even).
+__device__ __forceinline__ uint16_t f32_to_bf16_hw(float f)
+{
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+
+// silu(g) * u with g / (1 + e^-g) evaluated as g * rcp(1 + exp2(-g log2 e)): hardware exp2 and rcp,
+// each within 1 ulp of fp32, far below the bf16 rounding the result goes through.
+__device__ __forceinline__ float silu_mul_f32(float g, float u)
+{
+    const float t = __builtin_amdgcn_exp2f(g * -1.44269504088896340736f);
+    return g * __builtin_amdgcn_rcpf(1.f + t) * u;
 }
 
 __device__ __forceinline__ float wave_max(float v)

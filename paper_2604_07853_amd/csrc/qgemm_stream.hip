@@ -331,14 +331,14 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
                             v1 *= sxr * sw1;
                         }
                         if (EPI == QARL_EPI_SILU_MUL) {
-                            const float a = v0 / (1.f + expf(-v0)) * v1;
-                            ((uint16_t *)p.out)[orow * (N / 2) + n0] = (uint16_t)f32_to_bf16_bits(a);
+                            const float a = silu_mul_f32(v0, v1);
+                            ((uint16_t *)p.out)[orow * (N / 2) + n0] = f32_to_bf16_hw(a);
                         } else if (p.out_f32) {
                             ((float *)p.out)[orow * N + n0] = v0;
                             ((float *)p.out)[orow * N + n1] = v1;
                         } else {
-                            ((uint16_t *)p.out)[orow * N + n0] = (uint16_t)f32_to_bf16_bits(v0);
-                            ((uint16_t *)p.out)[orow * N + n1] = (uint16_t)f32_to_bf16_bits(v1);
+                            ((uint16_t *)p.out)[orow * N + n0] = f32_to_bf16_hw(v0);
+                            ((uint16_t *)p.out)[orow * N + n1] = f32_to_bf16_hw(v1);
                         }
                     }
                 }

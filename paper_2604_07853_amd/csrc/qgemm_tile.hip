@@ -3,14 +3,17 @@
 // codes and scales and with the same exact dequantized weight s*q, for experts that see
 // hundreds to thousands of token rows, where the path is a dense contraction.
 //
-// A workgroup owns a (32*MS)-token x 256-column tile of one expert.  Its wavefronts split the
-// columns: each owns 32*NT of them as MS x NT v_mfma_f32_32x32x16 tiles, so no packed weight is
-// read or expanded twice in a workgroup.  Token rows are gathered once per workgroup into a
+// A workgroup owns a (32*MS)-token x 256-column tile of one expert.  Its eight wavefronts split
+// the columns: each owns 32 of them as MS v_mfma_f32_32x32x16 tiles, so no packed weight is read
+// or expanded twice in a workgroup.  Token rows are gathered once per workgroup into a
 // double-buffered LDS tile (one 128-k scale group per step); packed weights go global ->
 // registers and are expanded there, so the LDS only carries the activation operand.  Small
-// wavefront tiles (NT = 1) keep the register count at 128, four wavefronts per SIMD from two
-// workgroups that run out of step: global-load latency and the VALU work of the expansion are
-// hidden by the other wavefronts' MFMAs rather than by a deep software pipeline.
+// wavefront tiles keep the register count at 128, four wavefronts per SIMD from two workgroups
+// that run out of step: global-load latency and the VALU work of the expansion are hidden by the
+// other wavefronts' MFMAs rather than by a deep software pipeline.  The kernel is bound by VALU
+// issue next to the MFMAs, so everything outside the k loop is kept short: the expert lookup is a
+// wavefront-level scan, output rows and activation scales wait in LDS, SiLU uses the hardware
+// exp2 / rcp, and gate and up meet through one 16-lane row swap.
 //
 // W4A16 group handling is the one described in qgemm_stream.hip: codes become the exact bf16
 // values (q+24)/16, every scale group accumulates in its own fp32 accumulator that starts at
@@ -21,6 +24,8 @@
 namespace qarl {
 
 constexpr int kBN = 256;
+constexpr int kTileWaves = kBN / 32;          // each wavefront owns 32 columns
+constexpr int kTileThreads = 64 * kTileWaves;
 constexpr int kAStrideB16 = kGroup * 2 + 16;  // bytes per LDS row, bf16 activations
 constexpr int kAStrideF8 = kGroup + 16;       // bytes per LDS row, e4m3 activations
 
@@ -40,21 +45,20 @@ struct TileParams {
     int total;      // n_blocks * m_slots rounded up to a multiple of 8
 };
 
-// MS: 32-row token tiles per wavefront; NT: 32-column tiles per wavefront (256/(32 NT) wavefronts).
-template <int FMT, int EPI, int MS, int NT>
-__global__ __launch_bounds__(64 * (kBN / (32 * NT)), (NT == 1 ? 4 : 2)) void qgemm_tile_kernel(TileParams p)
+// MS: 32-row token tiles per wavefront (workgroup tile = 32 MS tokens x 256 columns).
+template <int FMT, int EPI, int MS>
+__global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kernel(TileParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
     constexpr bool kSilu = (EPI == QARL_EPI_SILU_MUL);
-    constexpr int kWaves = kBN / (32 * NT);
-    constexpr int kThreads = 64 * kWaves;
     constexpr int kBM = 32 * MS;
+    constexpr int kThreads = kTileThreads;
     constexpr int kStride = kInt4 ? kAStrideB16 : kAStrideF8;
     constexpr int kBufBytes = kBM * kStride + kBM * 4;  // tile + per-row group sums
-    __shared__ int s_rows[kBM];
-    __shared__ int s_scan[256];
-    __shared__ int s_expert, s_mtile;
+    __shared__ __attribute__((aligned(16))) int s_rows[kBM];   // activation row of each tile row (clamped to a valid one)
+    __shared__ __attribute__((aligned(16))) int s_orow[kBM];   // output row, -1 past the expert's last row
+    __shared__ __attribute__((aligned(16))) float s_xs[kBM];   // fp8: activation scale of the row
 
     const int tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
@@ -67,95 +71,90 @@ __global__ __launch_bounds__(64 * (kBN / (32 * NT)), (NT == 1 ? 4 : 2)) void qge
     const int slot = v / p.n_blocks;
     if (slot >= p.m_slots) return;
 
-    // slot -> (expert, tile within expert) by a scan over the per-expert tile counts
-    if (tid < 256) {
-        int t = 0;
-        if (tid < p.E) t = (p.offsets[tid + 1] - p.offsets[tid] + kBM - 1) / kBM;
-        s_scan[tid] = t;
-    }
-    if (tid == 0) s_expert = -1;
-    lds_barrier();
-    for (int o = 1; o < 256; o <<= 1) {
-        int add = 0;
-        if (tid < 256 && tid >= o) add = s_scan[tid - o];
-        lds_barrier();
-        if (tid < 256) s_scan[tid] += add;
-        lds_barrier();
-    }
-    if (tid < p.E) {
-        const int incl = s_scan[tid];
-        const int excl = tid ? s_scan[tid - 1] : 0;
-        if (slot >= excl && slot < incl) {
-            s_expert = tid;
-            s_mtile = slot - excl;
+    // slot -> (expert, tile within expert): every wavefront scans the per-expert tile counts itself
+    // (four experts per lane, prefix sum across lanes), so no barrier is needed to agree on it.
+    int e, mtile;
+    {
+        int cnt[4], sum = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int ex = lane * 4 + q;
+            cnt[q] = ex < p.E ? (p.offsets[ex + 1] - p.offsets[ex] + kBM - 1) / kBM : 0;
+            sum += cnt[q];
         }
+        int incl = sum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        int base = incl - sum, found = -1, mt = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (slot >= base && slot < base + cnt[q]) {
+                found = lane * 4 + q;
+                mt = slot - base;
+            }
+            base += cnt[q];
+        }
+        const unsigned long long hit = __ballot(found >= 0);
+        if (hit == 0) return;
+        const int src = __ffsll((long long)hit) - 1;
+        e = __builtin_amdgcn_readfirstlane(__shfl(found, src, 64));
+        mtile = __builtin_amdgcn_readfirstlane(__shfl(mt, src, 64));
     }
-    lds_barrier();
-    const int e = s_expert;
-    if (e < 0) return;
-    const int row0 = p.offsets[e] + s_mtile * kBM;
+    const int row0 = p.offsets[e] + mtile * kBM;
     const int mrem = min(kBM, p.offsets[e + 1] - row0);
     if (tid < kBM) {
-        const int i = row0 + tid;
-        s_rows[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
+        // rows past the expert's end read the tile's first row (valid data, results never stored)
+        const int i = row0 + (tid < mrem ? tid : 0);
+        const int xrow = p.row_map ? p.row_map[i] : i;
+        s_rows[tid] = xrow;
+        s_orow[tid] = tid < mrem ? (p.out_row_map ? p.out_row_map[i] : i) : -1;
+        if (!kInt4) s_xs[tid] = p.x_scales[xrow];
     }
     lds_barrier();
 
     const int N = p.N, K = p.K, G = K / kGroup;
-    // Weight row of this lane in each of its column tiles (any row may feed any lane of the B
-    // operand).  SILU_MUL: gate row j and up row N/2 + j must meet in one lane or in lanes 16 apart:
-    //   NT = 2: tile 0 = 32 gate rows, tile 1 = the matching 32 up rows (same lane);
-    //   NT = 1: lanes c < 16 take 16 gate rows, lanes c >= 16 the matching up rows (lane ^ 16).
-    int nrow[NT];
-    bool tile_ok[NT];
+    // Weight row of this lane (any row may feed any lane of the B operand).  SILU_MUL: lanes c < 16
+    // take 16 gate rows, lanes c >= 16 the matching 16 up rows, so gate j and up j sit 16 lanes apart.
+    int nrow, ocol;
+    bool tile_ok;
     if (kSilu) {
-        if (NT == 2) {
-            nrow[0] = nb * (kBN / 2) + wn * 32 + c;
-            nrow[NT - 1] = N / 2 + nrow[0];
-            tile_ok[0] = tile_ok[NT - 1] = nrow[0] - c + 32 <= N / 2;
-        } else {
-            const int j = nb * (kBN / 2) + wn * 16 + (c & 15);
-            nrow[0] = (c < 16 ? 0 : N / 2) + j;
-            tile_ok[0] = j - (c & 15) + 16 <= N / 2;
-        }
+        ocol = nb * (kBN / 2) + wn * 16 + (c & 15);
+        nrow = (c < 16 ? 0 : N / 2) + ocol;
+        tile_ok = ocol - (c & 15) + 16 <= N / 2;
     } else {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            nrow[nt] = nb * kBN + wn * 32 * NT + nt * 32 + c;
-            tile_ok[nt] = nrow[nt] - c + 32 <= N;
-        }
+        ocol = nrow = nb * kBN + wn * 32 + c;
+        tile_ok = nrow - c + 32 <= N;
     }
-    const int words_per_row = kInt4 ? K / 8 : K / 4;
-    const uint32_t *wrow[NT], *wblk[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int64_t r = (int64_t)e * N + (tile_ok[nt] ? nrow[nt] : 0);
-        wrow[nt] = p.codes + r * words_per_row;                      // fp8: row-major
-        wblk[nt] = p.codes + (r / 16) * G * 256 + (r % 16) * 4;      // int4: first block of the row's tile
-    }
+    // columns past N read row 0 of the expert (valid data, results never stored)
+    const int64_t wr = (int64_t)e * N + (tile_ok ? nrow : 0);
+    // Byte offsets from the (uniform) array bases; the launcher checks that every array is below 4 GiB.
+    //   int4 codes: block (16-row tile, group g) is 1 KiB; this lane's row is wr % 16 of tile wr / 16 and it
+    //   takes the 16-byte pieces q = 2h + u (k in [32 q, +32)).  fp8 codes: row-major bytes, k in [64 h, +64).
+    uint32_t woff = kInt4 ? (uint32_t)((wr / 16) * G * 1024 + (wr % 16) * 16 + h * 512)
+                          : (uint32_t)(wr * K + h * 64);
+    uint32_t soff = (uint32_t)(wr * G * 2);   // int4: the row's bf16 scales
 
     // ---- activation tile: kBM rows x 128 k, 16-byte blocks; consecutive lanes cover one row
     constexpr int kBlkPerRow = kInt4 ? 16 : 8;
-    constexpr int kARegs = (kBM * kBlkPerRow + kThreads - 1) / kThreads;
+    static_assert((kBM * kBlkPerRow) % kThreads == 0, "tile / thread mismatch");
+    constexpr int kARegs = (kBM * kBlkPerRow) / kThreads;
     u32x4 ar[kARegs];
     float gsum = 0.f;  // W4A16: -1.5 * sum of this thread's row over the group (threads < kBM)
-    auto load_a = [&](int g) {
-        if (kInt4 && tid < kBM) {
-            const int xrow = s_rows[tid];
-            gsum = xrow >= 0 ? p.x_group_sums[(int64_t)xrow * G + g] : 0.f;
-        }
+    const unsigned char *arow[kARegs];
 #pragma unroll
-        for (int u = 0; u < kARegs; ++u) {
-            const int idx = u * kThreads + tid;
-            const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
-            ar[u] = u32x4{0, 0, 0, 0};
-            if (r < kBM) {
-                const int xrow = s_rows[r];
-                if (xrow >= 0)
-                    ar[u] = *(const u32x4 *)((const unsigned char *)p.x +
-                                             ((int64_t)xrow * K + g * kGroup) * (kInt4 ? 2 : 1) + b * 16);
-            }
-        }
+    for (int u = 0; u < kARegs; ++u) {
+        const int idx = u * kThreads + tid;
+        const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
+        arow[u] = (const unsigned char *)p.x + (int64_t)s_rows[r] * K * (kInt4 ? 2 : 1) + b * 16;
+    }
+    const float *gsrow = p.x_group_sums + (int64_t)s_rows[tid % kBM] * G;
+    auto load_a = [&](int g) {
+        if (kInt4 && tid < kBM) gsum = gsrow[g];
+#pragma unroll
+        for (int u = 0; u < kARegs; ++u) ar[u] = *(const u32x4 *)(arow[u] + g * kGroup * (kInt4 ? 2 : 1));
     };
     auto store_a = [&](int buf) {
         unsigned char *xs = smem + buf * kBufBytes;
@@ -165,184 +164,140 @@ __global__ __launch_bounds__(64 * (kBN / (32 * NT)), (NT == 1 ? 4 : 2)) void qge
         for (int u = 0; u < kARegs; ++u) {
             const int idx = u * kThreads + tid;
             const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
-            if (r < kBM) *(u32x4 *)(xs + r * kStride + b * 16) = ar[u];
+            *(u32x4 *)(xs + r * kStride + b * 16) = ar[u];
         }
     };
 
-    // ---- packed weights of one group: lane (c,h) reads k in [128 g + 64 h, +64) of its rows
-    constexpr int kWRegs = kInt4 ? 2 : 4;  // 16-byte loads per lane and column tile
+    // ---- packed weights of one group
+    constexpr int kWRegs = kInt4 ? 2 : 4;  // 16-byte loads per lane
     struct BRegs {
-        u32x4 w[NT][kWRegs];
-        uint32_t s[NT];
+        u32x4 w[kWRegs];
+        uint32_t s;
     };
     auto load_b = [&](BRegs &dst, int g) {
+        const unsigned char *wb = (const unsigned char *)p.codes;
+        const uint32_t o = woff + (uint32_t)g * (kInt4 ? 1024u : 128u);
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-            for (int u = 0; u < kWRegs; ++u) {
-                dst.w[nt][u] = u32x4{0, 0, 0, 0};
-                if (tile_ok[nt]) {
-                    // int4: block (16-row tile, group g) is 1 KiB; this lane's row is r % 16 of tile r / 16 and
-                    // it takes the 16-byte pieces q = 2h + u (k in [32 q, +32)).  fp8: row-major bytes.
-                    const uint32_t *src = kInt4 ? wblk[nt] + ((int64_t)g * 64 + (2 * h + u) * 16) * 4
-                                                : wrow[nt] + (g * 32 + h * 16 + u * 4);
-                    dst.w[nt][u] = *(const u32x4 *)src;
-                }
-            }
-            dst.s[nt] = 0;
-            if (kInt4 && tile_ok[nt]) dst.s[nt] = ((const uint16_t *)p.scales)[((int64_t)e * N + nrow[nt]) * G + g];
-        }
+        for (int u = 0; u < kWRegs; ++u) dst.w[u] = *(const u32x4 *)(wb + (o + (kInt4 ? u * 256u : u * 16u)));
+        dst.s = kInt4 ? *(const uint16_t *)((const unsigned char *)p.scales + (soff + (uint32_t)g * 2u)) : 0;
     };
 
-    f32x16 acc[MS][NT];
+    f32x16 acc[MS];
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[ms][nt][i] = 0.f;
+        for (int i = 0; i < 16; ++i) acc[ms][i] = 0.f;
 
-    BRegs bcur, bnxt;
-    load_a(0);
-    load_b(bcur, 0);
-    store_a(0);
-    lds_barrier();
-    for (int g = 0; g < G; ++g) {
-        if (g + 1 < G) {
-            load_a(g + 1);
-            load_b(bnxt, g + 1);
-        }
-        const unsigned char *xs = smem + (g & 1) * kBufBytes;
-        const float *sx = (const float *)(xs + kBM * kStride);
+    // One 128-k step on the LDS buffer `buf` with the weights in `b`.
+    const int afrag = c * kStride + h * (kInt4 ? 128 : 64);   // this lane's operand read: rows c (+32 ms), its half of the k range
+    auto step = [&](const BRegs &b, int buf) {
+        const unsigned char *xs = smem + buf * kBufBytes + afrag;
+        const float *sx = (const float *)(smem + buf * kBufBytes + kBM * kStride);
         if (kInt4) {
-            f32x16 ag[MS][NT];
+            f32x16 ag[MS];
 #pragma unroll
-            for (int ms = 0; ms < MS; ++ms) {
+            for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
                     const f32x4 init = *(const f32x4 *)(sx + ms * 32 + 8 * i4 + 4 * h);
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) ag[ms][nt][i4 * 4 + i] = init[i];
+                    for (int i = 0; i < 4; ++i) ag[ms][i4 * 4 + i] = init[i];
                 }
-            }
-            if (NT == 1) {
-                // four wavefronts per SIMD: the other wavefronts cover LDS latency and code expansion
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const bf16x8 b = unpack_int4_word(bcur.w[0][j >> 2][j & 3]);
-#pragma unroll
-                    for (int ms = 0; ms < MS; ++ms) {
-                        const bf16x8 a = *(const bf16x8 *)(xs + (ms * 32 + c) * kStride + (h * 64 + j * 8) * 2);
-                        ag[ms][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, ag[ms][0], 0, 0, 0);
-                    }
-                }
-            } else {
-            // Software pipeline over the eight 16-k slices: the LDS reads and the code expansion of
-            // slice j+1 are issued under the MFMAs of slice j; the group barriers pin that
-            // interleaving (MFMA, LDS read, VALU, MFMA, ...) in the machine schedule.
-            bf16x8 a_c[MS], b_c[NT];
-#pragma unroll
-            for (int ms = 0; ms < MS; ++ms) a_c[ms] = *(const bf16x8 *)(xs + (ms * 32 + c) * kStride + (h * 64) * 2);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) b_c[nt] = unpack_int4_word(bcur.w[nt][0][0]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                bf16x8 a_n[MS], b_n[NT];
-                if (j < 7) {
-#pragma unroll
-                    for (int ms = 0; ms < MS; ++ms)
-                        a_n[ms] = *(const bf16x8 *)(xs + (ms * 32 + c) * kStride + (h * 64 + (j + 1) * 8) * 2);
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) b_n[nt] = unpack_int4_word(bcur.w[nt][(j + 1) >> 2][(j + 1) & 3]);
-                }
-#pragma unroll
-                for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        ag[ms][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_c[ms], b_c[nt], ag[ms][nt], 0, 0, 0);
-                if (j < 7) {
-#pragma unroll
-                    for (int t = 0; t < MS * NT; ++t) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
-                        if (t < MS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);            // LDS read
-                        __builtin_amdgcn_sched_group_barrier(0x002, (8 * NT) / (MS * NT), 0);     // VALU
-                    }
-#pragma unroll
-                    for (int ms = 0; ms < MS; ++ms) a_c[ms] = a_n[ms];
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) b_c[nt] = b_n[nt];
-                }
-            }
-            }
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const float s16 = 16.f * bf16_bits_to_f32(bcur.s[nt]);
-#pragma unroll
-                for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[ms][nt][i] = fmaf(s16, ag[ms][nt][i], acc[ms][nt][i]);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                long b[NT];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const u32x4 w = bcur.w[nt][j >> 1];
-                    b[nt] = (long)(((uint64_t)w[(j & 1) * 2 + 1] << 32) | w[(j & 1) * 2]);
-                }
+                const bf16x8 bw = unpack_int4_word(b.w[j >> 2][j & 3]);
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms) {
-                    const long a = *(const long *)(xs + (ms * 32 + c) * kStride + h * 64 + j * 8);
+                    const bf16x8 a = *(const bf16x8 *)(xs + ms * 32 * kStride + j * 16);
+                    ag[ms] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bw, ag[ms], 0, 0, 0);
+                }
+            }
+            const float s16 = 16.f * bf16_bits_to_f32(b.s);
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        acc[ms][nt] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b[nt], acc[ms][nt], 0, 0, 0);
+            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[ms][i] = fmaf(s16, ag[ms][i], acc[ms][i]);
+        } else {
+            // lane (c,h): slice j covers the 8 bytes k in [64 h + 8 j, +8); one 16-byte read feeds two slices
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp) {
+                const u32x4 w = b.w[jp];
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms) {
+                    const u32x4 a = *(const u32x4 *)(xs + ms * 32 * kStride + jp * 16);
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const long av = (long)(((uint64_t)a[2 * t + 1] << 32) | a[2 * t]);
+                        const long bv = (long)(((uint64_t)w[2 * t + 1] << 32) | w[2 * t]);
+                        acc[ms] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(av, bv, acc[ms], 0, 0, 0);
+                    }
                 }
             }
         }
+    };
+
+    // Two steps per trip so that the two weight register sets swap roles without copies.
+    BRegs b0, b1;
+    load_a(0);
+    load_b(b0, 0);
+    store_a(0);
+    lds_barrier();
+    for (int g = 0; g < G; g += 2) {
         if (g + 1 < G) {
-            store_a((g + 1) & 1);
-            bcur = bnxt;
+            load_a(g + 1);
+            load_b(b1, g + 1);
         }
+        step(b0, 0);
+        if (g + 1 < G) store_a(1);
+        lds_barrier();
+        if (g + 1 >= G) break;
+        if (g + 2 < G) {
+            load_a(g + 2);
+            load_b(b0, g + 2);
+        }
+        step(b1, 1);
+        if (g + 2 < G) store_a(0);
         lds_barrier();
     }
 
-    // ---- epilogue: lane (c,h), register i -> token row 8*(i/4) + 4h + i%4, column c of each tile
-    float swn[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-        swn[nt] = (!kInt4 && tile_ok[nt]) ? ((const float *)p.scales)[(int64_t)e * N + nrow[nt]] : 1.f;
+    // ---- epilogue: lane (c,h), register i -> token row 8*(i/4) + 4h + i%4, column c of the tile
+    const float swn = kInt4 ? 1.f : ((const float *)p.scales)[wr];
+    const int ncols = kSilu ? N / 2 : N;
+    const int esz = (kSilu || !p.out_f32) ? 2 : 4;
+    unsigned char *obase = (unsigned char *)p.out + (int64_t)ocol * esz;
+    const uint32_t rstride = (uint32_t)ncols * (uint32_t)esz;   // bytes per output row (< 2^31: checked by the launcher)
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int r = ms * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-            const bool row_ok = r < mrem;
-            const int64_t srow = (int64_t)row0 + (row_ok ? r : 0);
-            const int64_t orow = p.out_row_map ? (int64_t)p.out_row_map[srow] : srow;
-            float vv[NT];
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const i32x4 orow4 = *(const i32x4 *)(s_orow + ms * 32 + 8 * i4 + 4 * h);
+            f32x4 vv;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                vv[nt] = acc[ms][nt][i];
-                if (!kInt4) vv[nt] *= (row_ok ? p.x_scales[s_rows[r]] : 0.f) * swn[nt];
+            for (int i = 0; i < 4; ++i) vv[i] = acc[ms][i4 * 4 + i];
+            if (!kInt4) {
+                const f32x4 xs4 = *(const f32x4 *)(s_xs + ms * 32 + 8 * i4 + 4 * h);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) vv[i] *= xs4[i] * swn;
             }
             if (kSilu) {
-                // gate and up value of the same column: tile 0 / tile 1 (NT = 2) or lanes 16 apart (NT = 1)
-                const float gate = vv[0];
-                const float up = (NT == 2) ? vv[NT - 1] : __shfl_xor(vv[0], 16, 64);
-                const bool writer = (NT == 2) || c < 16;
-                if (row_ok && tile_ok[0] && writer) {
-                    const float a = gate / (1.f + expf(-gate)) * up;
-                    ((uint16_t *)p.out)[orow * (N / 2) + nrow[0]] = (uint16_t)f32_to_bf16_bits(a);
+                // Registers i and i+1 trade 16-lane rows: afterwards every lane holds a gate value
+                // and the up value of the same column; lanes c < 16 for row i, lanes c >= 16 for row i+1.
+#pragma unroll
+                for (int ip = 0; ip < 2; ++ip) {
+                    const u32x2 sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(vv[2 * ip]),
+                                                                      __float_as_uint(vv[2 * ip + 1]), false, false);
+                    const int orow = c < 16 ? orow4[2 * ip] : orow4[2 * ip + 1];
+                    if (orow >= 0 && tile_ok) {
+                        const float a = silu_mul_f32(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                        *(uint16_t *)(obase + (uint64_t)(uint32_t)orow * rstride) = f32_to_bf16_hw(a);
+                    }
                 }
             } else {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    if (row_ok && tile_ok[nt]) {
-                        if (p.out_f32) ((float *)p.out)[orow * N + nrow[nt]] = vv[nt];
-                        else ((uint16_t *)p.out)[orow * N + nrow[nt]] = (uint16_t)f32_to_bf16_bits(vv[nt]);
+                for (int i = 0; i < 4; ++i) {
+                    if (orow4[i] >= 0 && tile_ok) {
+                        if (p.out_f32) *(float *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride) = vv[i];
+                        else *(uint16_t *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride) = f32_to_bf16_hw(vv[i]);
                     }
                 }
             }
@@ -350,18 +305,22 @@ __global__ __launch_bounds__(64 * (kBN / (32 * NT)), (NT == 1 ? 4 : 2)) void qge
     }
 }
 
-template <int FMT, int EPI, int MS, int NT>
+template <int FMT, int EPI, int MS>
 static int launch_cfg(const GemmArgs &a, hipStream_t s)
 {
     constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
     constexpr int kBM = 32 * MS;
-    constexpr int kThreads = 64 * (kBN / (32 * NT));
     if (a.E > 256) {
         set_error("qgemm (prefill path): at most 256 experts (got %d)", a.E);
         return QARL_ERR_UNSUPPORTED;
     }
-    if (a.N % 32 != 0) {
-        set_error("qgemm (prefill path): N %% 32 == 0 required (got %d)", a.N);
+    if (a.N % 32 != 0 || a.N > (1 << 28)) {
+        set_error("qgemm (prefill path): N %% 32 == 0 and N <= 2^28 required (got %d)", a.N);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    const int64_t n_w = (int64_t)a.E * a.N * a.K;
+    if ((kInt4 ? n_w / 2 : n_w) >= (1LL << 32)) {
+        set_error("qgemm (prefill path): quantized weights of one call must stay below 4 GiB");
         return QARL_ERR_UNSUPPORTED;
     }
     TileParams p;
@@ -387,24 +346,23 @@ static int launch_cfg(const GemmArgs &a, hipStream_t s)
     }
     p.m_slots = (int)slots;
     p.total = (int)total;
-    const int stride = kInt4 ? kAStrideB16 : kAStrideF8;
-    const size_t lds = 2 * ((size_t)kBM * stride + kBM * 4);
+    const size_t lds = 2 * ((size_t)kBM * (kInt4 ? kAStrideB16 : kAStrideF8) + kBM * 4);
     static bool attr_done = false;
-    auto kern = qgemm_tile_kernel<FMT, EPI, MS, NT>;
+    auto kern = qgemm_tile_kernel<FMT, EPI, MS>;
     if (!attr_done) {
         int rc = check_hip(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
                            "hipFuncSetAttribute(tile)");
         if (rc) return rc;
         attr_done = true;
     }
-    kern<<<dim3((unsigned)total), dim3(kThreads), lds, s>>>(p);
+    kern<<<dim3((unsigned)total), dim3(kTileThreads), lds, s>>>(p);
     return check_hip(hipGetLastError(), "qgemm_tile_kernel");
 }
 
 template <int FMT, int EPI>
 static int launch_one(const GemmArgs &a, hipStream_t s)
 {
-    return launch_cfg<FMT, EPI, 2, 1>(a, s);
+    return launch_cfg<FMT, EPI, 2>(a, s);
 }
 
 // sums[row][g] = -1.5 * sum over the 128 k of group g of x[row][k]: the start value of a group's
