@@ -141,7 +141,8 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
  * [seq_offsets[s], seq_offsets[s+1])) the sequence-level weight of section 3.2,
  * seq_w[s] = exp(mean_t delta[t]), with the two-sided cap seq_w_clipped[s] =
  * exp(clip(mean delta, -log c, log c)), c = tis_cap_c > 1.
- *   h bf16 [T][H], w_lm bf16 [V][H], target int32 [T]; H % 64 == 0.
+ *   h bf16 [T][H], w_lm bf16 [V][H], target int32 [T]; H % 64 == 0; inv_temperature > 0
+ *   and finite.  A target outside [0, V) gives logprob NaN for that token.
  *   delta, seq_w, seq_w_clipped may each be NULL; seq outputs need seq_offsets and S > 0. */
 int qarl_token_logprob(const void *h_bf16, const void *w_lm_bf16, const int32_t *target, int T,
                        int H, int V, float inv_temperature, float *logprob,

@@ -294,6 +294,10 @@ int qarl_token_logprob(const void *h_bf16, const void *w_lm_bf16, const int32_t 
         return QARL_ERR_INVALID_ARG;
     }
     if (T == 0) return QARL_OK;
+    if (!(inv_temperature > 0.f) || inv_temperature > 3.0e38f) {
+        set_error("qarl_token_logprob: inv_temperature must be positive and finite (got %g)", (double)inv_temperature);
+        return QARL_ERR_INVALID_ARG;
+    }
     if (!h_bf16 || !w_lm_bf16 || !target || !logprob) {
         set_error("qarl_token_logprob: null pointer");
         return QARL_ERR_INVALID_ARG;

@@ -1,179 +1,284 @@
-// LM head fused with the per-token log-prob: logits z = inv_T * h W^T are formed tile by
-// tile in fp32 MFMA accumulators and reduced on the spot to (row max, row sum of
-// exp(z - max)) per 256-column block plus the target logit; a second small kernel merges the
-// blocks: logprob = z_target - (m + log sum).  The [T][V] logits never reach memory.
-// This is the learner-forward half of the comparison in eq. (3).
+// LM head fused with the per-token log-prob: logits z = inv_T * h W^T are formed tile by tile
+// in fp32 MFMA accumulators and reduced on the spot to (max, sum of exp(z - max)) per token and
+// 256-row block of the vocabulary; a second small kernel merges the blocks and subtracts from the
+// target logit, which a third one computes as a plain dot product:
+//     logprob = z_target - (m + log sum).
+// The [T][V] logits never reach memory.  This is the learner-forward half of the comparison in
+// eq. (3).
+//
+// The big kernel is a dense bf16 contraction, D^T = W_tile (256 vocab rows) x h_tile^T (256 tokens):
+// vocabulary rows are the MFMA row operand, so that a lane ends up with 64 logits of ONE token per
+// token tile and the max / sum-exp reduction runs down its own registers; only the two 32-lane halves
+// and the two wavefronts that share a token meet through a shuffle and LDS.  Both operands reach LDS
+// by asynchronous global -> LDS copies (no staging registers), two 64-k stages deep; 16-byte chunks of
+// a row are XOR-swizzled with the row index so that the copies (8 rows x 128 bytes per wavefront
+// instruction, coalesced) and the operand reads (32 rows, one chunk) are both free of bank conflicts.
+// Operand reads run one 16-k slice ahead of the MFMAs, across the stage barrier as well.
 #include "common.hpp"
 
 namespace qarl {
 
 constexpr int kLThreads = 512;
-constexpr int kLBM = 128;
-constexpr int kLBN = 256;
-constexpr int kLKS = 64;                  // k per step
-constexpr int kLStride = kLKS * 2 + 16;   // LDS bytes per activation row
+constexpr int kLTile = 256;                 // vocabulary rows and tokens per workgroup
+constexpr int kLKS = 64;                    // k per stage
+constexpr int kLRowB = kLKS * 2;            // bytes per tile row and stage
+constexpr int kLTileB = kLTile * kLRowB;    // one operand tile of one stage
+constexpr int kLStageB = 2 * kLTileB;       // W tile, then h tile
+constexpr int kLLds = 2 * kLStageB;         // two stages
+constexpr int kLGroupM = 8, kLGroupN = 4;   // workgroups of one XCD that run together: 8 token x 4 vocab tiles
 
 struct LogprobParams {
     const uint16_t *h;
     const uint16_t *w;
-    const int32_t *target;
-    float *pmax, *psum, *tgt;  // [n_blocks][T], [n_blocks][T], [T]
-    int T, H, V, n_blocks, m_tiles, total;
+    float *pmax, *psum;  // [n_blocks][T]
+    int T, H, V, n_blocks, m_tiles, n_mgroups;
     float inv_temp;
 };
 
-__global__ __launch_bounds__(kLThreads, 1) void lmhead_lse_kernel(LogprobParams p)
+__device__ __forceinline__ void copy16_to_lds(const void *gsrc, void *lds_dst)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char xs_all[2 * kLBM * kLStride];
-    __shared__ float s_m[4][kLBM], s_s[4][kLBM];
+    // lane L's 16 bytes land at lds_dst + 16 L; lds_dst is the same in all lanes; counted by vmcnt
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                     (__attribute__((address_space(3))) void *)lds_dst, 16, 0, 0);
+}
+
+__global__ __launch_bounds__(kLThreads, 2) void lmhead_lse_kernel(LogprobParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave >> 2, wt = wave & 3;   // 128 vocabulary rows x 64 tokens per wavefront
     const int c = lane & 31, h = lane >> 5;
 
-    // consecutive workgroup ids go round-robin over the 8 XCDs: hand each XCD a contiguous range of
-    // tiles, token tiles fastest, so the token tiles that share a block of W_lm share an L2.
-    const int per_xcd = p.total / 8;
-    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    const int mt = v % p.m_tiles, nb = v / p.m_tiles;
-    if (nb >= p.n_blocks) return;
+    // Consecutive workgroup ids go round-robin over the 8 XCDs.  The workgroups that run together on one
+    // XCD (32 CUs, one workgroup each) form an 8-token-tile x 4-vocabulary-tile block, so that its L2
+    // fetches 12 operand tiles for 32 output tiles.
+    const int xcd = blockIdx.x % 8, idx = blockIdx.x / 8;
+    const int super = (idx / (kLGroupM * kLGroupN)) * 8 + xcd, within = idx % (kLGroupM * kLGroupN);
+    const int mt = (super % p.n_mgroups) * kLGroupM + within % kLGroupM;
+    const int nb = (super / p.n_mgroups) * kLGroupN + within / kLGroupM;
+    if (mt >= p.m_tiles || nb >= p.n_blocks) return;
 
     const int T = p.T, H = p.H, V = p.V;
-    const int row0 = mt * kLBM;
-    int col[2];
-    col[0] = nb * kLBN + wn * 64 + c;
-    col[1] = col[0] + 32;
-    const bool col_ok[2] = {col[0] < V, col[1] < V};
-    const u32x4 *wrow[2];
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) wrow[nt] = (const u32x4 *)(p.w + (int64_t)(col_ok[nt] ? col[nt] : 0) * H);
+    const int v0 = nb * kLTile, t0 = mt * kLTile;
 
-    u32x4 ar[2];
-    auto load_a = [&](int ks) {
+    // ---- copies: a wavefront instruction moves 8 rows x 128 bytes; this wavefront owns rows
+    // [32 wave, 32 wave + 32) of both tiles.  Chunk q of row r sits at r * 128 + (q ^ ((r >> 1) & 7)) * 16.
+    uint32_t woff[4], hoff[4];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int idx = u * kLThreads + tid;
-            const int r = idx >> 3, b = idx & 7;
-            ar[u] = u32x4{0, 0, 0, 0};
-            if (row0 + r < T) ar[u] = *(const u32x4 *)(p.h + (int64_t)(row0 + r) * H + ks * kLKS + b * 8);
-        }
-    };
-    auto store_a = [&](int buf) {
+    for (int i = 0; i < 4; ++i) {
+        const int r = wave * 32 + i * 8 + (lane >> 3);
+        const int q = (lane & 7) ^ ((r >> 1) & 7);
+        woff[i] = (uint32_t)min(r, V - 1 - v0) * (uint32_t)(H * 2) + q * 16;   // rows past V or T read the last
+        hoff[i] = (uint32_t)min(r, T - 1 - t0) * (uint32_t)(H * 2) + q * 16;   // valid row: never used
+    }
+    const unsigned char *wbase = (const unsigned char *)p.w + (int64_t)v0 * H * 2;
+    const unsigned char *hbase = (const unsigned char *)p.h + (int64_t)t0 * H * 2;
+    auto copy_stage = [&](int ks, int buf) {
+        unsigned char *dst = smem + buf * kLStageB + wave * 32 * kLRowB;
+        const unsigned char *ws = wbase + (int64_t)ks * kLRowB, *hs = hbase + (int64_t)ks * kLRowB;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int idx = u * kLThreads + tid;
-            const int r = idx >> 3, b = idx & 7;
-            *(u32x4 *)(xs_all + buf * kLBM * kLStride + r * kLStride + b * 16) = ar[u];
-        }
-    };
-    struct BRegs {
-        u32x4 w[2][4];
-    };
-    auto load_b = [&](BRegs &dst, int ks) {
+        for (int i = 0; i < 4; ++i) copy16_to_lds(ws + woff[i], dst + i * 8 * kLRowB);
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                dst.w[nt][j] = u32x4{0, 0, 0, 0};
-                if (col_ok[nt]) dst.w[nt][j] = wrow[nt][ks * (kLKS / 8) + h * 4 + j];
-            }
+        for (int i = 0; i < 4; ++i) copy16_to_lds(hs + hoff[i], dst + kLTileB + i * 8 * kLRowB);
     };
 
-    f32x16 acc[2][2];
+    // ---- operand reads: lane (c,h) takes row c of a 32-row tile, k in [16 j + 8 h, +8) = chunk 2j + h
+    int aoff[4];
 #pragma unroll
-    for (int ms = 0; ms < 2; ++ms)
+    for (int j = 0; j < 4; ++j) aoff[j] = c * kLRowB + (((2 * j + h) ^ ((c >> 1) & 7)) * 16);
+    const int a_wave = wm * 128 * kLRowB, b_wave = kLTileB + wt * 64 * kLRowB;
+    struct Frags {
+        bf16x8 a[4], b[2];
+    };
+    auto read_frags = [&](Frags &f, int buf, int j) {
+        const unsigned char *base = smem + buf * kLStageB + aoff[j];
+#pragma unroll
+        for (int ms = 0; ms < 4; ++ms) f.a[ms] = *(const bf16x8 *)(base + a_wave + ms * 32 * kLRowB);
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) f.b[nt] = *(const bf16x8 *)(base + b_wave + nt * 32 * kLRowB);
+    };
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int ms = 0; ms < 4; ++ms)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[ms][nt][i] = 0.f;
+    auto mfma8 = [&](const Frags &f) {
+#pragma unroll
+        for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+                acc[ms][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ms], f.b[nt], acc[ms][nt], 0, 0, 0);
+    };
+    auto stage_barrier = [&]() {
+        // own copies landed, own operand reads done; then everybody's
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
 
-    const int steps = H / kLKS;
-    BRegs bcur, bnxt;
-    load_a(0);
-    load_b(bcur, 0);
-    store_a(0);
-    lds_barrier();
-    for (int ks = 0; ks < steps; ++ks) {
-        if (ks + 1 < steps) {
-            load_a(ks + 1);
-            load_b(bnxt, ks + 1);
-        }
-        const unsigned char *xs = xs_all + (ks & 1) * kLBM * kLStride;
+    // Rotated loop: the MFMAs of a stage's last slice run in the next trip, behind the stage barrier and
+    // under the first operand reads of the next stage, so no operand read is outstanding at the back edge
+    // and every wait inside the trip counts exactly the reads it needs.
+    const int stages = H / kLKS;
+    Frags last, f0, f1, f2, f3;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bf16x8 b0 = __builtin_bit_cast(bf16x8, bcur.w[0][j]);
-            const bf16x8 b1 = __builtin_bit_cast(bf16x8, bcur.w[1][j]);
+    for (int i = 0; i < 4; ++i) last.a[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int ms = 0; ms < 2; ++ms) {
-                const bf16x8 a = *(const bf16x8 *)(xs + (wm * 64 + ms * 32 + c) * kLStride + (h * 32 + j * 8) * 2);
-                acc[ms][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[ms][0], 0, 0, 0);
-                acc[ms][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[ms][1], 0, 0, 0);
-            }
-        }
-        if (ks + 1 < steps) {
-            store_a((ks + 1) & 1);
-            bcur = bnxt;
-        }
-        lds_barrier();
+    for (int i = 0; i < 2; ++i) last.b[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    copy_stage(0, 0);
+    stage_barrier();
+    for (int ks = 0; ks < stages; ++ks) {
+        const int buf = ks & 1;
+        if (ks + 1 < stages) copy_stage(ks + 1, buf ^ 1);
+        read_frags(f0, buf, 0);
+        mfma8(last);
+        // one MFMA, the six operand reads of the next slice, the other seven MFMAs: the wait in front of
+        // a slice then finds only reads issued seven MFMAs earlier
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(f1, buf, 1);
+        mfma8(f0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(f2, buf, 2);
+        mfma8(f1);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(f3, buf, 3);
+        mfma8(f2);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        stage_barrier();
+        last = f3;
     }
+    mfma8(last);
 
-    // ---- per-row (max, sum exp) over this workgroup's 256 columns, and the target logit
+    // ---- per token: max and sum of exp over this wavefront's 128 vocabulary rows.
+    // lane (c,h), register i of acc[ms][nt] -> vocabulary row v0 + 128 wm + 32 ms + 8 (i/4) + 4 h + i%4,
+    // token t0 + 64 wt + 32 nt + c.  exp(inv_T (a - m)) = exp2(k a - k m), k = inv_T log2 e > 0.
+    float *s_m = (float *)smem, *s_s = s_m + 2 * kLTile;   // [wm][token] (the tiles are dead by now)
+    const float k2 = p.inv_temp * 1.44269504088896340736f;
+    const int vrow_lane = v0 + wm * 128 + 4 * h;
+    const bool ragged = v0 + kLTile > V;
 #pragma unroll
-    for (int ms = 0; ms < 2; ++ms) {
+    for (int nt = 0; nt < 2; ++nt) {
+        if (ragged) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int r = wm * 64 + ms * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-            const float z0 = col_ok[0] ? acc[ms][0][i] * p.inv_temp : -INFINITY;
-            const float z1 = col_ok[1] ? acc[ms][1][i] * p.inv_temp : -INFINITY;
-            if (row0 + r < T) {
-                const int y = p.target[row0 + r];
-                if (y == col[0]) p.tgt[row0 + r] = z0;
-                if (y == col[1]) p.tgt[row0 + r] = z1;
-            }
-            float m = fmaxf(z0, z1);
+            for (int ms = 0; ms < 4; ++ms)
 #pragma unroll
-            for (int o = 1; o < 32; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-            float s = 0.f;
-            if (m > -INFINITY) s = expf(z0 - m) + expf(z1 - m);
-#pragma unroll
-            for (int o = 1; o < 32; o <<= 1) s += __shfl_xor(s, o, 64);
-            if (c == 0) {
-                s_m[wn][r] = m;
-                s_s[wn][r] = s;
-            }
+                for (int i = 0; i < 16; ++i)
+                    if (vrow_lane + ms * 32 + 8 * (i >> 2) + (i & 3) >= V) acc[ms][nt][i] = -INFINITY;
         }
-    }
-    lds_barrier();
-    if (tid < kLBM && row0 + tid < T) {
-        float m = fmaxf(fmaxf(s_m[0][tid], s_m[1][tid]), fmaxf(s_m[2][tid], s_m[3][tid]));
+        float m = -INFINITY;
+#pragma unroll
+        for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) m = fmaxf(m, acc[ms][nt][i]);
+        m = fmaxf(m, __shfl_xor(m, 32, 64));   // the other 64 rows of this token
         float s = 0.f;
+        if (m > -INFINITY) {
+            const float mk = m * k2;
 #pragma unroll
-        for (int w4 = 0; w4 < 4; ++w4)
-            if (s_m[w4][tid] > -INFINITY) s += s_s[w4][tid] * expf(s_m[w4][tid] - m);
-        p.pmax[(int64_t)nb * T + row0 + tid] = m;
-        p.psum[(int64_t)nb * T + row0 + tid] = s;
+            for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s += __builtin_amdgcn_exp2f(fmaf(acc[ms][nt][i], k2, -mk));
+        }
+        s += __shfl_xor(s, 32, 64);
+        if (h == 0) {
+            s_m[wm * kLTile + wt * 64 + nt * 32 + c] = m;
+            s_s[wm * kLTile + wt * 64 + nt * 32 + c] = s;
+        }
+    }
+    lds_barrier();
+    if (tid < kLTile && t0 + tid < T) {
+        const float m0 = s_m[tid], m1 = s_m[kLTile + tid];
+        const float m = fmaxf(m0, m1);
+        float s = 0.f;
+        if (m0 > -INFINITY) s += s_s[tid] * __builtin_amdgcn_exp2f((m0 - m) * k2);
+        if (m1 > -INFINITY) s += s_s[kLTile + tid] * __builtin_amdgcn_exp2f((m1 - m) * k2);
+        p.pmax[(int64_t)nb * T + t0 + tid] = m * p.inv_temp;
+        p.psum[(int64_t)nb * T + t0 + tid] = s;
     }
 }
 
-// Merge the per-block partials of one token (fixed order) and emit the log-prob.
+// Target logit of each token: inv_T * <h_t, w_{y_t}> in fp32, one wavefront per token.  A target outside
+// [0, V) yields NaN.
+__global__ __launch_bounds__(256) void target_logit_kernel(const uint16_t *__restrict__ hmat,
+                                                           const uint16_t *__restrict__ w,
+                                                           const int32_t *__restrict__ target, int T, int H, int V,
+                                                           float inv_temp, float *__restrict__ tgt)
+{
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (t >= T) return;
+    const int y = target[t];
+    if (y < 0 || y >= V) {
+        if (lane == 0) tgt[t] = __uint_as_float(0x7fc00000u);
+        return;
+    }
+    const u32x4 *hr = (const u32x4 *)(hmat + (int64_t)t * H), *wr = (const u32x4 *)(w + (int64_t)y * H);
+    float s = 0.f;
+    for (int q = lane; q < H / 8; q += 64) {
+        const u32x4 a = hr[q], b = wr[q];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            s = fmaf(__uint_as_float(a[i] << 16), __uint_as_float(b[i] << 16), s);
+            s = fmaf(__uint_as_float(a[i] & 0xffff0000u), __uint_as_float(b[i] & 0xffff0000u), s);
+        }
+    }
+    s = wave_sum(s);
+    if (lane == 0) tgt[t] = s * inv_temp;
+}
+
+// Merge the per-block partials of one token and emit the log-prob.  64 tokens per workgroup; four
+// threads per token each fold every fourth block into a running (max, sum), and the four meet in LDS in
+// a fixed order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void lse_finalize_kernel(const float *__restrict__ pmax,
                                                            const float *__restrict__ psum,
                                                            const float *__restrict__ tgt, int T, int n_blocks,
                                                            float *__restrict__ logprob)
 {
-    const int t = blockIdx.x * 256 + threadIdx.x;
-    if (t >= T) return;
-    float m = -INFINITY;
-    for (int b = 0; b < n_blocks; ++b) m = fmaxf(m, pmax[(int64_t)b * T + t]);
-    double s = 0.0;
-    for (int b = 0; b < n_blocks; ++b) s += (double)psum[(int64_t)b * T + t] * (double)expf(pmax[(int64_t)b * T + t] - m);
-    logprob[t] = tgt[t] - (m + (float)log(s));
+    __shared__ float s_m[4][64], s_s[4][64];
+    const int tl = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int t = blockIdx.x * 64 + tl;
+    float m = -INFINITY, s = 0.f;
+    if (t < T) {
+        for (int b = slice; b < n_blocks; b += 4) {
+            const float mb = pmax[(int64_t)b * T + t], sb = psum[(int64_t)b * T + t];
+            if (mb > m) {
+                s = s * expf(m - mb) + sb;   // exp(-inf) = 0 on the first block
+                m = mb;
+            } else if (mb > -INFINITY) {
+                s += sb * expf(mb - m);
+            }
+        }
+    }
+    s_m[slice][tl] = m;
+    s_s[slice][tl] = s;
+    __syncthreads();
+    if (slice == 0 && t < T) {
+        float mm = fmaxf(fmaxf(s_m[0][tl], s_m[1][tl]), fmaxf(s_m[2][tl], s_m[3][tl]));
+        double ss = 0.0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (s_m[q][tl] > -INFINITY) ss += (double)s_s[q][tl] * (double)expf(s_m[q][tl] - mm);
+        logprob[t] = tgt[t] - (mm + (float)log(ss));
+    }
 }
 
 size_t logprob_ws_bytes(int T, int H, int V)
 {
     (void)H;
-    const size_t nb = (size_t)(V + kLBN - 1) / kLBN;
+    const size_t nb = (size_t)(V + kLTile - 1) / kLTile;
     return (2 * nb + 1) * (size_t)T * sizeof(float);
 }
 
@@ -183,26 +288,42 @@ int launch_logprob(const void *h, const void *wlm, const int32_t *target, int T,
     LogprobParams p;
     p.h = (const uint16_t *)h;
     p.w = (const uint16_t *)wlm;
-    p.target = target;
     p.T = T;
     p.H = H;
     p.V = V;
-    p.n_blocks = (V + kLBN - 1) / kLBN;
-    p.m_tiles = (T + kLBM - 1) / kLBM;
+    p.n_blocks = (V + kLTile - 1) / kLTile;
+    p.m_tiles = (T + kLTile - 1) / kLTile;
+    p.n_mgroups = (p.m_tiles + kLGroupM - 1) / kLGroupM;
     p.pmax = (float *)ws;
     p.psum = p.pmax + (size_t)p.n_blocks * T;
-    p.tgt = p.psum + (size_t)p.n_blocks * T;
+    float *tgt = p.psum + (size_t)p.n_blocks * T;
     p.inv_temp = inv_temp;
-    const int64_t total = (((int64_t)p.n_blocks * p.m_tiles + 7) / 8) * 8;
-    if (total > 0x7fffffffLL) {
+    if ((int64_t)kLTile * H * 2 >= (1LL << 31)) {
+        set_error("logprob: H too large");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    const int64_t n_ngroups = (p.n_blocks + kLGroupN - 1) / kLGroupN;
+    const int64_t supers = (((int64_t)p.n_mgroups * n_ngroups + 7) / 8) * 8;
+    const int64_t grid = supers * kLGroupM * kLGroupN;
+    if (grid > 0x7fffffffLL) {
         set_error("logprob: grid too large");
         return QARL_ERR_UNSUPPORTED;
     }
-    p.total = (int)total;
-    lmhead_lse_kernel<<<dim3((unsigned)total), dim3(kLThreads), 0, s>>>(p);
-    int rc = check_hip(hipGetLastError(), "lmhead_lse_kernel");
+    static bool attr_done = false;
+    if (!attr_done) {
+        int rc = check_hip(hipFuncSetAttribute((const void *)lmhead_lse_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               kLLds),
+                           "hipFuncSetAttribute(lmhead)");
+        if (rc) return rc;
+        attr_done = true;
+    }
+    target_logit_kernel<<<dim3((T + 3) / 4), dim3(256), 0, s>>>(p.h, p.w, target, T, H, V, inv_temp, tgt);
+    int rc = check_hip(hipGetLastError(), "target_logit_kernel");
     if (rc) return rc;
-    lse_finalize_kernel<<<dim3((T + 255) / 256), dim3(256), 0, s>>>(p.pmax, p.psum, p.tgt, T, p.n_blocks, logprob);
+    lmhead_lse_kernel<<<dim3((unsigned)grid), dim3(kLThreads), kLLds, s>>>(p);
+    rc = check_hip(hipGetLastError(), "lmhead_lse_kernel");
+    if (rc) return rc;
+    lse_finalize_kernel<<<dim3((T + 63) / 64), dim3(256), 0, s>>>(p.pmax, p.psum, tgt, T, p.n_blocks, logprob);
     return check_hip(hipGetLastError(), "lse_finalize_kernel");
 }
 
