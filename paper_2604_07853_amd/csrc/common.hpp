@@ -89,6 +89,22 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Asynchronous global -> LDS copy of one wavefront: active lane L's 16 bytes land at lds_dst + 16 L.
+// lds_dst must be the same in all lanes.  Completion is counted by vmcnt, in order with the
+// wavefront's other vector loads.
+__device__ __forceinline__ void copy16_to_lds(const void *gsrc, void *lds_dst)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                     (__attribute__((address_space(3))) void *)lds_dst, 16, 0, 0);
+}
+
+// Barrier for LDS buffers filled by copy16_to_lds: every wavefront first waits for its own copies
+// (and LDS operations), then for the others.
+__device__ __forceinline__ void copy_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Host-side error plumbing (api.hip).
 void set_error(const char *fmt, ...);
 int check_hip(hipError_t e, const char *what);

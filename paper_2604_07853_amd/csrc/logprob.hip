@@ -35,13 +35,6 @@ struct LogprobParams {
     float inv_temp;
 };
 
-__device__ __forceinline__ void copy16_to_lds(const void *gsrc, void *lds_dst)
-{
-    // lane L's 16 bytes land at lds_dst + 16 L; lds_dst is the same in all lanes; counted by vmcnt
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
-                                     (__attribute__((address_space(3))) void *)lds_dst, 16, 0, 0);
-}
-
 __global__ __launch_bounds__(kLThreads, 2) void lmhead_lse_kernel(LogprobParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];

@@ -19,6 +19,50 @@ __device__ __forceinline__ uint32_t sort_key(uint32_t h, int id)
     return (k << 16) | (0xffffu - (uint32_t)id);
 }
 
+// Wavefront reductions on the data-parallel-primitive path (row shifts inside 16-lane rows, then two
+// row broadcasts); the result is read from lane 63 into a scalar, so it is uniform.  `ident` fills the
+// lanes a shift has no source for.
+#define QARL_DPP_STEP(T, OP, CTRL, ROWMASK)                                                                   \
+    v = OP(v, (T)__builtin_bit_cast(T, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, ident),             \
+                                                                   __builtin_bit_cast(int, v), CTRL, ROWMASK, 0xf, false)))
+__device__ __forceinline__ uint32_t umax2(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ float fadd2(float a, float b) { return a + b; }
+__device__ __forceinline__ uint32_t wave_max_u32_dpp(uint32_t v)
+{
+    const uint32_t ident = 0;
+    QARL_DPP_STEP(uint32_t, umax2, 0x111, 0xf);  // row_shr:1
+    QARL_DPP_STEP(uint32_t, umax2, 0x112, 0xf);  // row_shr:2
+    QARL_DPP_STEP(uint32_t, umax2, 0x114, 0xf);  // row_shr:4
+    QARL_DPP_STEP(uint32_t, umax2, 0x118, 0xf);  // row_shr:8
+    QARL_DPP_STEP(uint32_t, umax2, 0x142, 0xa);  // row_bcast:15 into rows 1 and 3
+    QARL_DPP_STEP(uint32_t, umax2, 0x143, 0xc);  // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+__device__ __forceinline__ float wave_max_f32_dpp(float v)
+{
+    const float ident = -INFINITY;
+    QARL_DPP_STEP(float, fmaxf, 0x111, 0xf);
+    QARL_DPP_STEP(float, fmaxf, 0x112, 0xf);
+    QARL_DPP_STEP(float, fmaxf, 0x114, 0xf);
+    QARL_DPP_STEP(float, fmaxf, 0x118, 0xf);
+    QARL_DPP_STEP(float, fmaxf, 0x142, 0xa);
+    QARL_DPP_STEP(float, fmaxf, 0x143, 0xc);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+// Sum in the fixed order the shifts imply; every lane gets the same value.
+__device__ __forceinline__ float wave_sum_f32_dpp(float v)
+{
+    const float ident = 0.f;
+    QARL_DPP_STEP(float, fadd2, 0x111, 0xf);
+    QARL_DPP_STEP(float, fadd2, 0x112, 0xf);
+    QARL_DPP_STEP(float, fadd2, 0x114, 0xf);
+    QARL_DPP_STEP(float, fadd2, 0x118, 0xf);
+    QARL_DPP_STEP(float, fadd2, 0x142, 0xa);
+    QARL_DPP_STEP(float, fadd2, 0x143, 0xc);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+#undef QARL_DPP_STEP
+
 __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(const uint16_t *__restrict__ logits, int T,
                                                                   int E, int topk, int renorm,
                                                                   int32_t *__restrict__ ids,
@@ -45,12 +89,12 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(const uint16_
     float m = -INFINITY;
 #pragma unroll
     for (int j = 0; j < kMaxPerLane; ++j) m = fmaxf(m, val[j]);
-    m = wave_max(m);
+    m = wave_max_f32_dpp(m);
     float z = 0.f;
 #pragma unroll
     for (int j = 0; j < kMaxPerLane; ++j)
         if (j < per) z += expf(val[j] - m);
-    z = wave_sum(z);
+    z = wave_sum_f32_dpp(z);
 
     int my_id = 0;      // lane r keeps the r-th winner
     float my_p = 0.f;
@@ -59,8 +103,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(const uint16_
         uint32_t best = 0;
 #pragma unroll
         for (int j = 0; j < kMaxPerLane; ++j) best = max(best, key[j]);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) best = max(best, (uint32_t)__shfl_xor((int)best, o, 64));
+        best = wave_max_u32_dpp(best);
         const int e = 0xffff - (int)(best & 0xffffu);
         // the owner retires the winner and publishes its logit
         float lv = 0.f;
@@ -70,7 +113,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(const uint16_
                 lv = val[j];
                 key[j] = 0;
             }
-        lv = __shfl(lv, e & 63, 64);
+        lv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lv), e & 63));
         const float p = expf(lv - m) / z;
         psum += p;
         if (lane == r) {
@@ -81,7 +124,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(const uint16_
     if (lane < topk) {
         ids[(int64_t)t * topk + lane] = my_id;
         wts[(int64_t)t * topk + lane] = renorm ? my_p / psum : my_p;
-        atomicAdd(&counts[my_id], 1);
+        if (counts) atomicAdd(&counts[my_id], 1);
     }
 }
 
@@ -162,14 +205,107 @@ __global__ __launch_bounds__(kGroupThreads) void group_by_expert_kernel(const in
     }
 }
 
+// Grouping for small batches (decode) by ONE workgroup, with no zeroing pass and no global atomics.
+// A token selects an expert at most once, so the pairs of an expert are ordered by token alone: the
+// workgroup builds a bit matrix B[expert][token] in LDS (atomic OR, order-free), prefix pop-counts per
+// 32-token word give every word's start inside its expert, a scan over the experts gives the offsets, and
+// a pair (t, slot) of expert e lands at offsets[e] + start[e][t / 32] + popcount(B[e][t / 32] below bit t):
+// the same stable order (expert, token, slot) the large-batch kernels produce.
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallMaxT = 512;
+constexpr int kSmallWords = kSmallMaxT / 32;
+constexpr int kSmallMaxPairs = 4096;
+
+__global__ __launch_bounds__(kSmallThreads) void group_small_kernel(const int32_t *__restrict__ ids, int T, int E,
+                                                                   int topk, int32_t *__restrict__ counts,
+                                                                   int32_t *__restrict__ offsets,
+                                                                   int32_t *__restrict__ pairs,
+                                                                   int32_t *__restrict__ tokens)
+{
+    __shared__ uint32_t s_bits[256 * kSmallWords];
+    __shared__ uint16_t s_start[256 * kSmallWords];
+    __shared__ int s_off[257];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n_pairs = T * topk, words = (T + 31) / 32;
+    for (int i = tid; i < E * words; i += kSmallThreads) s_bits[i] = 0;
+    __syncthreads();
+    constexpr int kMine = kSmallMaxPairs / kSmallThreads;
+    int my_e[kMine];
+#pragma unroll
+    for (int u = 0; u < kMine; ++u) {
+        const int pidx = tid + u * kSmallThreads;
+        my_e[u] = -1;
+        if (pidx < n_pairs) {
+            const int e = ids[pidx], t = pidx / topk;
+            my_e[u] = e;
+            atomicOr(&s_bits[e * words + (t >> 5)], 1u << (t & 31));
+        }
+    }
+    __syncthreads();
+    if (tid < E) {
+        int run = 0;
+        for (int w = 0; w < words; ++w) {
+            s_start[tid * words + w] = (uint16_t)run;
+            run += __popc(s_bits[tid * words + w]);
+        }
+        counts[tid] = run;
+        s_off[tid + 1] = run;
+    }
+    if (tid == 0) s_off[0] = 0;
+    __syncthreads();
+    if (tid < 64) {   // inclusive scan of the counts over the experts, four per lane
+        int v[4], sum = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            v[j] = (lane * 4 + j < E) ? s_off[lane * 4 + j + 1] : 0;
+            sum += v[j];
+        }
+        int incl = sum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        int run = incl - sum;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            run += v[j];
+            if (lane * 4 + j < E) s_off[lane * 4 + j + 1] = run;
+        }
+    }
+    __syncthreads();
+    if (tid <= E) offsets[tid] = s_off[tid];
+#pragma unroll
+    for (int u = 0; u < kMine; ++u) {
+        const int pidx = tid + u * kSmallThreads;
+        const int e = my_e[u];
+        if (e >= 0) {
+            const int t = pidx / topk;
+            const uint32_t below = s_bits[e * words + (t >> 5)] & ((1u << (t & 31)) - 1u);
+            const int pos = s_off[e] + s_start[e * words + (t >> 5)] + __popc(below);
+            pairs[pos] = pidx;
+            tokens[pos] = t;
+        }
+    }
+}
+
 int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w,
                  int32_t *counts, int32_t *offsets, int32_t *pairs, int32_t *tokens, hipStream_t s)
 {
+    const int per_block = kRouteThreads / 64;
+    const int64_t n_pairs = (int64_t)T * topk;
+    if (T > 0 && T <= kSmallMaxT && n_pairs <= kSmallMaxPairs) {
+        route_topk_kernel<<<dim3((T + per_block - 1) / per_block), dim3(kRouteThreads), 0, s>>>(
+            (const uint16_t *)logits, T, E, topk, renorm, ids, w, nullptr);
+        int rc = check_hip(hipGetLastError(), "route_topk_kernel");
+        if (rc) return rc;
+        group_small_kernel<<<dim3(1), dim3(kSmallThreads), 0, s>>>(ids, T, E, topk, counts, offsets, pairs, tokens);
+        return check_hip(hipGetLastError(), "group_small_kernel");
+    }
     zero_i32_kernel<<<dim3((E + 255) / 256), dim3(256), 0, s>>>(counts, E);
     int rc = check_hip(hipGetLastError(), "zero_i32_kernel");
     if (rc) return rc;
     if (T > 0) {
-        const int per_block = kRouteThreads / 64;
         route_topk_kernel<<<dim3((T + per_block - 1) / per_block), dim3(kRouteThreads), 0, s>>>(
             (const uint16_t *)logits, T, E, topk, renorm, ids, w, counts);
         rc = check_hip(hipGetLastError(), "route_topk_kernel");
