@@ -399,8 +399,7 @@ int launch_qgemm_tile(const GemmArgs &a, hipStream_t s)
     if (a.fmt == QARL_W4A16_G128)
         return a.epilogue == QARL_EPI_SILU_MUL ? launch_one<QARL_W4A16_G128, QARL_EPI_SILU_MUL>(a, s)
                                                : launch_one<QARL_W4A16_G128, QARL_EPI_NONE>(a, s);
-    return a.epilogue == QARL_EPI_SILU_MUL ? launch_one<QARL_FP8_E4M3_CH, QARL_EPI_SILU_MUL>(a, s)
-                                           : launch_one<QARL_FP8_E4M3_CH, QARL_EPI_NONE>(a, s);
+    return launch_qgemm_tile_fp8(a, s);
 }
 
 }  // namespace qarl

@@ -1,0 +1,368 @@
+// Grouped quantized GEMM, MFMA-tiled ("prefill" / training-forward) path for the FP8 W8A8 format:
+// eq. (2) of section 2.2 with e4m3 activations (one scale per token row) and e4m3 weights (one scale
+// per output channel), Y = s_x s_w (X_q W_q^T), on the same codes and scales as the streaming path.
+//
+// Both operands are MFMA inputs as stored, so the kernel is a plain dense contraction: a workgroup owns
+// 128 token rows x 256 weight rows of one expert; its eight wavefronts (2 x 4) own 64 x 64 each as 2 x 2
+// v_mfma_f32_32x32x64_f8f6f4 tiles (e4m3 x e4m3, unit block scales).  Token rows (gathered through row_map) and weight rows reach LDS by
+// asynchronous global -> LDS copies, three 128-k stages deep; 16-byte chunks of a row are XOR-swizzled with
+// the row index so that the copies (8 rows x 128 bytes per wavefront instruction) and the operand reads
+// (32 rows, one chunk) are free of bank conflicts.  The operand reads of half a stage run under the MFMAs
+// of the half before, across the stage barrier as well.
+#include "common.hpp"
+
+namespace qarl {
+
+constexpr int kFThreads = 512;
+constexpr int kFTM = 128, kFTN = 256;        // token rows, weight rows per workgroup
+constexpr int kFKS = 128;                    // k (= bytes) per stage
+constexpr int kFStageB = (kFTM + kFTN) * kFKS;
+constexpr int kFStages = 3;
+constexpr int kFLds = kFStages * kFStageB;
+
+struct Tile8Params {
+    const unsigned char *codes;   // [E][N][K] e4m3
+    const float *scales;          // [E][N]
+    const unsigned char *x;       // [x_rows][K] e4m3
+    const float *x_scales;        // [x_rows]
+    const int32_t *row_map;
+    const int32_t *out_row_map;
+    const int32_t *offsets;
+    void *out;
+    int E, N, K, out_f32;
+    int n_blocks;   // column blocks per expert
+    int bpw;        // consecutive column blocks one workgroup computes
+    int n_bgroups;  // ceil(n_blocks / bpw)
+    int m_slots, total;
+};
+
+template <int EPI>
+__global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Params p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr bool kSilu = (EPI == QARL_EPI_SILU_MUL);
+    __shared__ __attribute__((aligned(16))) int s_rows[kFTM];
+    __shared__ __attribute__((aligned(16))) int s_orow[kFTM];
+    __shared__ __attribute__((aligned(16))) float s_xs[kFTM];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int c = lane & 31, h = lane >> 5;
+
+    // workgroup id -> (m slot, column block); XCD-contiguous ranges, column blocks of a token tile adjacent
+    const int per_xcd = p.total / 8;
+    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int nb0 = (v % p.n_bgroups) * p.bpw;
+    const int slot = v / p.n_bgroups;
+    if (slot >= p.m_slots) return;
+
+    // slot -> (expert, tile within expert): wavefront-level scan of the per-expert tile counts
+    int e, mtile;
+    {
+        int cnt[4], sum = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int ex = lane * 4 + q;
+            cnt[q] = ex < p.E ? (p.offsets[ex + 1] - p.offsets[ex] + kFTM - 1) / kFTM : 0;
+            sum += cnt[q];
+        }
+        int incl = sum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        int base = incl - sum, found = -1, mt = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (slot >= base && slot < base + cnt[q]) {
+                found = lane * 4 + q;
+                mt = slot - base;
+            }
+            base += cnt[q];
+        }
+        const unsigned long long hit = __ballot(found >= 0);
+        if (hit == 0) return;
+        const int src = __ffsll((long long)hit) - 1;
+        e = __builtin_amdgcn_readfirstlane(__shfl(found, src, 64));
+        mtile = __builtin_amdgcn_readfirstlane(__shfl(mt, src, 64));
+    }
+    const int row0 = p.offsets[e] + mtile * kFTM;
+    const int mrem = min(kFTM, p.offsets[e + 1] - row0);
+    if (tid < kFTM) {
+        // rows past the expert's end read the tile's first row (valid data, results never stored)
+        const int i = row0 + (tid < mrem ? tid : 0);
+        const int xrow = p.row_map ? p.row_map[i] : i;
+        s_rows[tid] = xrow;
+        s_orow[tid] = tid < mrem ? (p.out_row_map ? p.out_row_map[i] : i) : -1;
+        s_xs[tid] = p.x_scales[xrow];
+    }
+    lds_barrier();
+
+    const int N = p.N, K = p.K;
+    // LDS weight row rho (0..255) of this workgroup -> weight row of the expert.  SILU_MUL: every 32-row
+    // tile holds 16 gate rows then the 16 matching up rows, so gate j and up j sit 16 lanes apart in the
+    // MFMA result.  Rows past N read row 0 (valid data, results never stored).
+    auto weight_row = [&](int nb, int rho) -> int {
+        int n;
+        bool ok;
+        if (kSilu) {
+            const int j = nb * (kFTN / 2) + (rho >> 5) * 16 + (rho & 15);
+            n = ((rho & 16) ? N / 2 : 0) + j;
+            ok = j - (rho & 15) + 16 <= N / 2;
+        } else {
+            n = nb * kFTN + rho;
+            ok = n - (rho & 31) + 32 <= N;
+        }
+        return ok ? n : 0;
+    };
+
+    // ---- copies: a wavefront instruction moves 8 rows x 128 bytes.  Chunk q of row r sits at
+    // r * 128 + (q ^ ((r >> 1) & 7)) * 16.  This wavefront copies token rows [16 w, 16 w + 16) and weight
+    // rows [32 w, 32 w + 32) of the tile.
+    const unsigned char *aptr[2];
+    uint32_t boff[4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = wave * 16 + i * 8 + (lane >> 3);
+        const int q = (lane & 7) ^ ((r >> 1) & 7);
+        aptr[i] = p.x + (int64_t)s_rows[r] * K + q * 16;
+    }
+    auto set_block = [&](int nb) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = wave * 32 + i * 8 + (lane >> 3);
+            const int q = (lane & 7) ^ ((r >> 1) & 7);
+            boff[i] = (uint32_t)weight_row(nb, r) * (uint32_t)K + q * 16;
+        }
+    };
+    set_block(nb0);
+    const unsigned char *wbase = p.codes + (int64_t)e * N * K;
+    auto copy_stage = [&](int ks, int buf) {
+        unsigned char *dst = smem + buf * kFStageB;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) copy16_to_lds(aptr[i] + ks * kFKS, dst + (wave * 16 + i * 8) * kFKS);
+        const unsigned char *ws = wbase + (int64_t)ks * kFKS;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) copy16_to_lds(ws + boff[i], dst + (kFTM + wave * 32 + i * 8) * kFKS);
+    };
+
+    // ---- operand reads: v_mfma_f32_32x32x64_f8f6f4 takes 32 bytes per lane and operand: lane (c,h), half t of
+    // the stage -> row c, bytes [64 t + 32 h, +32) = chunks 4t + 2h and 4t + 2h + 1 (both operands split k alike)
+    int foff[4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) foff[t * 2 + u] = c * kFKS + (((4 * t + 2 * h + u) ^ ((c >> 1) & 7)) * 16);
+    const int a_wave = wm * 64 * kFKS, b_wave = (kFTM + wn * 64) * kFKS;
+    struct Frags {
+        i32x8 a[2], b[2];
+    };
+    auto read_frags = [&](Frags &f, int buf, int t) {
+        const unsigned char *base = smem + buf * kFStageB;
+#pragma unroll
+        for (int ms = 0; ms < 2; ++ms) {
+            const u32x4 lo = *(const u32x4 *)(base + foff[t * 2] + a_wave + ms * 32 * kFKS);
+            const u32x4 hi = *(const u32x4 *)(base + foff[t * 2 + 1] + a_wave + ms * 32 * kFKS);
+            f.a[ms] = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+        }
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const u32x4 lo = *(const u32x4 *)(base + foff[t * 2] + b_wave + nt * 32 * kFKS);
+            const u32x4 hi = *(const u32x4 *)(base + foff[t * 2 + 1] + b_wave + nt * 32 * kFKS);
+            f.b[nt] = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+        }
+    };
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int ms = 0; ms < 2; ++ms)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ms][nt][i] = 0.f;
+    auto mfma4 = [&](const Frags &f) {
+#pragma unroll
+        for (int ms = 0; ms < 2; ++ms)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)   // e4m3 x e4m3, no block scales
+                acc[ms][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.a[ms], f.b[nt], acc[ms][nt], 0, 0, 0, 0, 0, 0);
+    };
+
+    // Rotated loop (see logprob.hip): the MFMAs of a stage's last group run in the next trip, behind the
+    // stage barrier and under the first operand reads of the next stage.  The copies of stage s + 2 are
+    // issued at the start of stage s into the buffer stage s - 1 has just left; the wait before the barrier
+    // leaves exactly those six copies in flight.
+    const int stages = K / kFKS;
+    Frags last, g0, g1;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        last.a[i] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+        last.b[i] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    auto start_block = [&]() {   // first two stages of a column block into buffers 0 and 1
+        copy_stage(0, 0);
+        if (stages > 1) copy_stage(1, 1);
+    };
+    start_block();
+  for (int bi = 0; bi < p.bpw && nb0 + bi < p.n_blocks; ++bi) {
+    const int nb = nb0 + bi;
+    if (stages > 1)
+        asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");   // stage 0 has landed (stores of the block before too)
+    else
+        copy_barrier();
+#pragma unroll
+    for (int ms = 0; ms < 2; ++ms)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ms][nt][i] = 0.f;
+    int buf = 0;
+    for (int ks = 0; ks < stages; ++ks) {
+        const bool more = ks + 2 < stages;
+        if (more) copy_stage(ks + 2, buf == 0 ? 2 : buf - 1);
+        read_frags(g0, buf, 0);
+        mfma4(last);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA, the eight operand reads of the next
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);   // half, the other three MFMAs
+        __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(g1, buf, 1);
+        mfma4(g0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more)
+            asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else
+            copy_barrier();
+        last = g1;
+        buf = buf == 2 ? 0 : buf + 1;
+    }
+    mfma4(last);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        last.a[i] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+        last.b[i] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+
+    // ---- epilogue: lane (c,h), register i -> token row 64 wm + 32 ms + 8 (i/4) + 4 h + i%4, column c of tile nt.
+    // The first copies of the next column block are issued first (every buffer is free after the last
+    // barrier), so they travel while this block's results are scaled and stored.
+    float swn2[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) swn2[nt] = p.scales[(int64_t)e * N + weight_row(nb, wn * 64 + nt * 32 + c)];
+    if (bi + 1 < p.bpw && nb + 1 < p.n_blocks) {
+        set_block(nb + 1);
+        start_block();
+    }
+    const int ncols = kSilu ? N / 2 : N;
+    const int esz = (kSilu || !p.out_f32) ? 2 : 4;
+    const uint32_t rstride = (uint32_t)ncols * (uint32_t)esz;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int rho = wn * 64 + nt * 32 + c;
+        int ocol;
+        bool tile_ok;
+        if (kSilu) {
+            ocol = nb * (kFTN / 2) + (rho >> 5) * 16 + (rho & 15);
+            tile_ok = ocol - (rho & 15) + 16 <= N / 2;
+        } else {
+            ocol = nb * kFTN + rho;
+            tile_ok = ocol - (rho & 31) + 32 <= N;
+        }
+        const float swn = swn2[nt];
+        unsigned char *obase = (unsigned char *)p.out + (int64_t)ocol * esz;
+#pragma unroll
+        for (int ms = 0; ms < 2; ++ms) {
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int rbase = wm * 64 + ms * 32 + 8 * i4 + 4 * h;
+                const i32x4 orow4 = *(const i32x4 *)(s_orow + rbase);
+                const f32x4 xs4 = *(const f32x4 *)(s_xs + rbase);
+                f32x4 vv;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) vv[i] = acc[ms][nt][i4 * 4 + i] * (xs4[i] * swn);
+                if (kSilu) {
+                    // registers i and i+1 trade 16-lane rows: every lane then holds a gate value and the up
+                    // value of the same column; lanes c < 16 for row i, lanes c >= 16 for row i+1
+#pragma unroll
+                    for (int ip = 0; ip < 2; ++ip) {
+                        const u32x2 sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(vv[2 * ip]),
+                                                                          __float_as_uint(vv[2 * ip + 1]), false, false);
+                        const int orow = (c & 16) ? orow4[2 * ip + 1] : orow4[2 * ip];
+                        if (orow >= 0 && tile_ok) {
+                            const float a = silu_mul_f32(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                            *(uint16_t *)(obase + (uint64_t)(uint32_t)orow * rstride) = f32_to_bf16_hw(a);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (orow4[i] >= 0 && tile_ok) {
+                            if (p.out_f32) *(float *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride) = vv[i];
+                            else *(uint16_t *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride) = f32_to_bf16_hw(vv[i]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+  }
+}
+
+template <int EPI>
+static int launch_fp8_cfg(const GemmArgs &a, hipStream_t s)
+{
+    if (a.E > 256) {
+        set_error("qgemm (prefill path): at most 256 experts (got %d)", a.E);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (a.N % 32 != 0 || a.N > (1 << 28) || (int64_t)a.N * a.K >= (1LL << 32)) {
+        set_error("qgemm (prefill path): N %% 32 == 0 and N * K < 2^32 required (got N=%d K=%d)", a.N, a.K);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    Tile8Params p;
+    p.codes = (const unsigned char *)a.codes;
+    p.scales = (const float *)a.scales;
+    p.x = (const unsigned char *)a.x;
+    p.x_scales = a.x_scales;
+    p.row_map = a.row_map;
+    p.out_row_map = a.out_row_map;
+    p.offsets = a.offsets;
+    p.out = a.out;
+    p.E = a.E;
+    p.N = a.N;
+    p.K = a.K;
+    p.out_f32 = a.out_f32;
+    p.n_blocks = (EPI == QARL_EPI_SILU_MUL) ? (a.N / 2 + kFTN / 2 - 1) / (kFTN / 2) : (a.N + kFTN - 1) / kFTN;
+    const int64_t slots = (a.M + kFTM - 1) / kFTM + a.E;
+    // a workgroup computes bpw neighbouring column blocks of its token tile one after the other: the expert
+    // lookup and the row gather are paid once, and a block's stores hide the first copies of the next
+    p.bpw = p.n_blocks >= 6 ? 3 : (p.n_blocks >= 2 ? 2 : 1);
+    p.n_bgroups = (p.n_blocks + p.bpw - 1) / p.bpw;
+    const int64_t total = ((slots * p.n_bgroups + 7) / 8) * 8;
+    if (total > 0x7fffffffLL) {
+        set_error("qgemm (prefill path): grid too large");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    p.m_slots = (int)slots;
+    p.total = (int)total;
+    static bool attr_done = false;
+    auto kern = qgemm_tile_fp8_kernel<EPI>;
+    if (!attr_done) {
+        int rc = check_hip(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kFLds),
+                           "hipFuncSetAttribute(tile fp8)");
+        if (rc) return rc;
+        attr_done = true;
+    }
+    kern<<<dim3((unsigned)total), dim3(kFThreads), kFLds, s>>>(p);
+    return check_hip(hipGetLastError(), "qgemm_tile_fp8_kernel");
+}
+
+int launch_qgemm_tile_fp8(const GemmArgs &a, hipStream_t s)
+{
+    return a.epilogue == QARL_EPI_SILU_MUL ? launch_fp8_cfg<QARL_EPI_SILU_MUL>(a, s) : launch_fp8_cfg<QARL_EPI_NONE>(a, s);
+}
+
+}  // namespace qarl
