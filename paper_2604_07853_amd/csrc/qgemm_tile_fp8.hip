@@ -300,8 +300,8 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         if (orow4[i] >= 0 && tile_ok) {
-                            if (p.out_f32) *(float *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride) = vv[i];
-                            else *(uint16_t *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride) = f32_to_bf16_hw(vv[i]);
+                            if (p.out_f32) __builtin_nontemporal_store(vv[i], (float *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride));
+                            else __builtin_nontemporal_store(f32_to_bf16_hw(vv[i]), (uint16_t *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride));
                         }
                     }
                 }

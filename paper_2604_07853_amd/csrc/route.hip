@@ -134,9 +134,27 @@ __global__ void zero_i32_kernel(int32_t *p, int n)
     if (i < n) p[i] = 0;
 }
 
+// Per-expert pair counts for large batches: every workgroup histograms its share of the ids in LDS and adds
+// its E partial counts to the global ones, so a popular expert's counter sees one add per workgroup instead
+// of one per routed token.
+constexpr int kCountThreads = 1024;
+constexpr int kCountBlocks = 64;
+
+__global__ __launch_bounds__(kCountThreads) void count_experts_kernel(const int32_t *__restrict__ ids, int n_pairs,
+                                                                     int E, int32_t *__restrict__ counts)
+{
+    __shared__ int s_hist[256];
+    if (threadIdx.x < 256) s_hist[threadIdx.x] = 0;
+    __syncthreads();
+    for (int i = blockIdx.x * kCountThreads + threadIdx.x; i < n_pairs; i += kCountBlocks * kCountThreads)
+        atomicAdd(&s_hist[ids[i]], 1);
+    __syncthreads();
+    if (threadIdx.x < E && s_hist[threadIdx.x] != 0) atomicAdd(&counts[threadIdx.x], s_hist[threadIdx.x]);
+}
+
 // One workgroup per expert: its offset is the sum of the counts before it; it then walks all
 // pairs in ascending order and compacts the ones routed to it, which keeps (t, slot) order.
-constexpr int kGroupThreads = 256;
+constexpr int kGroupThreads = 1024;
 constexpr int kPairsPerThread = 4;
 
 __global__ __launch_bounds__(kGroupThreads) void group_by_expert_kernel(const int32_t *__restrict__ ids,
@@ -307,8 +325,11 @@ int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t
     if (rc) return rc;
     if (T > 0) {
         route_topk_kernel<<<dim3((T + per_block - 1) / per_block), dim3(kRouteThreads), 0, s>>>(
-            (const uint16_t *)logits, T, E, topk, renorm, ids, w, counts);
+            (const uint16_t *)logits, T, E, topk, renorm, ids, w, nullptr);
         rc = check_hip(hipGetLastError(), "route_topk_kernel");
+        if (rc) return rc;
+        count_experts_kernel<<<dim3(kCountBlocks), dim3(kCountThreads), 0, s>>>(ids, (int)n_pairs, E, counts);
+        rc = check_hip(hipGetLastError(), "count_experts_kernel");
         if (rc) return rc;
     }
     group_by_expert_kernel<<<dim3(E), dim3(kGroupThreads), 0, s>>>(ids, T * topk, E, topk, counts, offsets,
