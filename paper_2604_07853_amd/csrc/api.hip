@@ -222,6 +222,7 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
     a.out_row_map = nullptr;
     a.offsets = expert_offsets;
     a.M = M;
+    a.x_rows = x_rows;
     a.epilogue = epilogue;
     a.out = out;
     a.out_f32 = (out_dtype == QARL_OUT_F32);

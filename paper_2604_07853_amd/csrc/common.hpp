@@ -127,6 +127,7 @@ struct GemmArgs {
     const int32_t *out_row_map;  // scatter of output rows, or null
     const int32_t *offsets;
     int64_t M;
+    int64_t x_rows;     // rows of x (bound of row_map values)
     int epilogue;       // NONE or SILU_MUL here; COMBINE is NONE into ws + combine kernel
     void *out;          // [M][N] or [M][N/2]
     int out_f32;

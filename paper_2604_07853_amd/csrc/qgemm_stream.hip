@@ -51,11 +51,11 @@ struct StreamParams {
 // LDS bytes per activation row: the row plus 16 bytes, so consecutive rows skew by 4 banks.
 __host__ __device__ constexpr int x_stride(bool int4, int K) { return K * (int4 ? 2 : 1) + 16; }
 
-// Dynamic LDS of a workgroup: row ids, int4 group sums, int4 per-wavefront scale buffers, token tile.
+// Dynamic LDS of a workgroup: row ids, output rows, fp8 row scales, int4 group sums, int4 per-wavefront scale buffers, token tile.
 static size_t stream_lds_bytes(bool int4, int K, int MT)
 {
     const size_t G = K / kGroup, rows = (size_t)MT * 16;
-    return rows * 4 + 16 + (int4 ? G * rows * 4 + (size_t)kSWaves * 2 * 32 * G * 2 : 0) + rows * x_stride(int4, K);
+    return rows * 12 + 16 + (int4 ? G * rows * 4 + (size_t)kSWaves * 2 * 32 * G * 2 : 0) + rows * x_stride(int4, K);
 }
 
 // FMT: weight format; EPI: NONE or SILU_MUL; MT: 16-row token tiles per block; R: ring depth in
@@ -81,12 +81,14 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
     if (unit_id >= p.E * p.n_slices) return;
     const int e = unit_id / p.n_slices, slice = unit_id % p.n_slices;
 
-    int *s_row = (int *)smem;                              // [kRowsMax]
-    int *s_next = (int *)(smem + kRowsMax * 4);            // next undrawn pair
-    float *sx = (float *)(smem + kRowsMax * 4 + 16);       // int4: [G][kRowsMax]  -1.5 * group sums
+    int *s_row = (int *)smem;                              // [kRowsMax] activation row of each tile row
+    int *s_orow = (int *)(smem + kRowsMax * 4);            // [kRowsMax] output row, -1 past the expert's last row
+    float *s_xs = (float *)(smem + kRowsMax * 8);          // [kRowsMax] fp8: activation scale of the row
+    int *s_next = (int *)(smem + kRowsMax * 12);           // next undrawn pair
+    float *sx = (float *)(smem + kRowsMax * 12 + 16);      // int4: [G][kRowsMax]  -1.5 * group sums
     // int4: per wavefront two buffers of [2 tiles][16 rows][G] bf16 scales (this pair, next pair)
-    uint16_t *ssc = (uint16_t *)(smem + kRowsMax * 4 + 16 + (kInt4 ? G * kRowsMax * 4 : 0)) + (kInt4 ? wave * 2 * 32 * G : 0);
-    unsigned char *xs = smem + kRowsMax * 4 + 16 + (kInt4 ? G * kRowsMax * 4 + kSWaves * 2 * 32 * G * 2 : 0);  // [kRowsMax][stride]
+    uint16_t *ssc = (uint16_t *)(smem + kRowsMax * 12 + 16 + (kInt4 ? G * kRowsMax * 4 : 0)) + (kInt4 ? wave * 2 * 32 * G : 0);
+    unsigned char *xs = smem + kRowsMax * 12 + 16 + (kInt4 ? G * kRowsMax * 4 + kSWaves * 2 * 32 * G * 2 : 0);  // [kRowsMax][stride]
 
     // this workgroup's pairs of weight tiles: units u_lo .. u_hi-1
     const int per_slice = (p.n_units + p.n_slices - 1) / p.n_slices;
@@ -177,6 +179,8 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
         if (tid < kRowsMax) {
             const int i = row0 + m0 + tid;
             s_row[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
+            s_orow[tid] = (tid < mrem) ? (p.out_row_map ? p.out_row_map[i] : i) : -1;
+            if (!kInt4) s_xs[tid] = (tid < mrem) ? p.x_scales[p.row_map ? p.row_map[i] : i] : 0.f;
         }
         if (tid == 0) *s_next = kSWaves;  // pairs 0..7 start on wavefronts 0..7, the rest are drawn
         lds_barrier();
@@ -321,12 +325,11 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_kernel(StreamParams
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int r = mt * 16 + 4 * q + i;
-                    if (r < mrem) {
-                        const int64_t srow = (int64_t)row0 + m0 + r;
-                        const int64_t orow = p.out_row_map ? (int64_t)p.out_row_map[srow] : srow;
+                    const int64_t orow = s_orow[r];
+                    if (orow >= 0) {
                         float v0 = acc[0][mt][i], v1 = acc[1][mt][i];
                         if (!kInt4) {
-                            const float sxr = p.x_scales[s_row[r]];
+                            const float sxr = s_xs[r];
                             v0 *= sxr * sw0;
                             v1 *= sxr * sw1;
                         }
