@@ -221,3 +221,36 @@ def test_empty_and_error_paths(q):
     with pytest.raises(q.QarlError) as ei:
         q.qarl_qgemm_grouped(qw, x, off, 4, epilogue=q.QARL_EPI_SILU_MUL, out_dtype=q.QARL_OUT_F32)
     assert ei.value.status == q.QARL_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("fmt", ["int4", "fp8"])
+@pytest.mark.parametrize("E,N,K,rows", [(3, 96, 128, (37, 0, 5)), (2, 288, 384, (300, 129)), (1, 32, 128, (1,)),
+                                        (2, 544, 768, (64, 257))])
+def test_ragged_shapes_both_paths(q, oracle, fmt, E, N, K, rows):
+    """Shapes that leave partial column tiles (N not a multiple of the tile width), a single 128-k stage,
+    empty experts, one-row experts and experts spanning several token tiles; plain epilogue, fp32 out."""
+    seed = 700 + N + K
+    w = synth.normal_bf16((E, N, K), 0.02, seed=seed)
+    M = int(sum(rows))
+    x = synth.normal_bf16((M, K), 1.0, seed=seed + 1)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    if fmt == "int4":
+        codes, scales = oracle.quantize_int4(np_bits(w))
+        ref = oracle.qgemm_w4a16(np_bits(x), codes, scales, off)
+        qw = q.qarl_quantize_weights(w.cuda())
+        xin, xs, tol = x.cuda(), None, TOL_F32
+    else:
+        wq, sw = oracle.quantize_fp8_rows(np_bits(w))
+        xq_ref, sx_ref = oracle.quantize_fp8_rows(np_bits(x))
+        ref = oracle.qgemm_fp8(xq_ref, sx_ref, wq, sw, off)
+        qw = q.qarl_quantize_weights(w.cuda(), q.QARL_FP8_E4M3_CH)
+        xin, xs = q.qarl_quantize_rows_fp8(x.cuda())
+        tol = TOL_F32_FP8
+    for path in _paths(q):
+        try:
+            y = q.qarl_qgemm_grouped(qw, xin, _i32(off), M, x_scales=xs, out_dtype=q.QARL_OUT_F32, path=path)
+        except q.QarlError as err:      # the streaming path takes W4A16 only with K a multiple of 256
+            assert path == q.QARL_PATH_DECODE and err.status == q.QARL_ERR_UNSUPPORTED and fmt == "int4" and K % 256
+            continue
+        e = norm_err(y.cpu().numpy(), ref)
+        assert e <= tol, (path, e)
