@@ -165,7 +165,7 @@ def main():
         "config": {"workload": "moe_decode_w4a16: 256 tokens, 128 experts x (gate_up [1536,2048] + down [2048,768]) "
                                "int4 g128, top-8, bf16 out", "tokens": T, "experts": E, "active_experts": active,
                    "weight_copies": args.copies, "step_bytes": step_bytes, "step_flop": synth.flops_moe(T)},
-        "roofline": {"bound": "hbm", "kernel": "qgemm_stream_kernel<W4A16, SILU_MUL> (gate_up)",
+        "roofline": {"bound": "hbm", "kernel": "qgemm_stream_w4_kernel<SILU_MUL> (gate_up)",
                      "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": GATE_UP_TRAFFIC_BYTES,
                      "bytes_per_launch": gu_bytes, "ms_per_launch": round(ms_gu, 5),

@@ -134,6 +134,8 @@ struct GemmArgs {
 };
 int launch_qgemm_stream(const GemmArgs &a, hipStream_t s);
 bool qgemm_stream_supported(int fmt, int N, int K);
+int launch_qgemm_stream_w4(const GemmArgs &a, hipStream_t s);
+bool qgemm_stream_w4_supported(int N, int K);
 int launch_qgemm_tile(const GemmArgs &a, hipStream_t s);
 int launch_qgemm_tile_fp8(const GemmArgs &a, hipStream_t s);
 int launch_group_sums(const void *x_bf16, int64_t rows, int K, float *sums, hipStream_t s);
