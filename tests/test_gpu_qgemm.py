@@ -254,3 +254,38 @@ def test_ragged_shapes_both_paths(q, oracle, fmt, E, N, K, rows):
             continue
         e = norm_err(y.cpu().numpy(), ref)
         assert e <= tol, (path, e)
+
+
+@pytest.mark.parametrize("E,N,K,T,topk", [(8, 64, 2048, 600, 3),     # row maps too large to sit beside the LDS tile
+                                          (4, 64, 512, 37, 3),       # M = 111: last quad of the map is partial
+                                          (16, 32, 256, 1500, 3),    # M = 4500: maps stay in global memory
+                                          (6, 96, 768, 171, 5)])     # 64-row blocks (K fits), M = 855
+def test_decode_row_map_paths(q, oracle, E, N, K, T, topk):
+    """Decode path with the gather map (routed tokens) and the scatter map (pair order of the combine):
+    every way the kernel fetches its row ids (copied to LDS next to the tile, into the tile region, or read
+    from global memory), experts that need several row blocks and several passes, M not a multiple of 4."""
+    seed = 900 + K + T
+    w = synth.normal_bf16((E, N, K), 0.02, seed=seed)
+    x = synth.normal_bf16((T, K), 1.0, seed=seed + 1)
+    lg = synth.router_logits(T, E, seed + 2, zipf_s=1.1)
+    ids, wts = oracle.route(np_bits(lg), topk)                     # the router kernel takes E % 64 == 0 only:
+    counts, offsets, pairs = oracle.group(ids, E)                  # the oracle's routing is this test's input
+    M = T * topk
+    tok = (pairs // topk).astype(np.int32)
+    d_off, d_tok, d_pairs = _i32(offsets), _i32(tok), _i32(pairs)
+    d_w = torch.tensor(np.asarray(wts, dtype=np.float32), device="cuda")
+    codes, scales = oracle.quantize_int4(np_bits(w))
+    qw = q.qarl_quantize_weights(w.cuda())
+    # gather only: rows of x picked through row_map, fp32 out in sorted order
+    y_ref = oracle.qgemm_w4a16(np_bits(x), codes, scales, offsets, tok)
+    y = q.qarl_qgemm_grouped(qw, x.cuda(), d_off, M, row_map=d_tok, out_dtype=q.QARL_OUT_F32,
+                             path=q.QARL_PATH_DECODE)
+    assert norm_err(y.cpu().numpy(), y_ref) <= TOL_F32
+    # gather + scatter: the same product through the combine epilogue (out_row_map = sorted pairs)
+    xg = x[torch.tensor(tok, dtype=torch.long)].contiguous()       # rows already in sorted order
+    y2_ref = oracle.qgemm_w4a16(np_bits(xg), codes, scales, offsets)
+    out_ref, out_ref_bits = oracle.combine(y2_ref, pairs, wts, T, topk)
+    out = q.qarl_qgemm_grouped(qw, xg.cuda(), d_off, M, epilogue=q.QARL_EPI_COMBINE, combine_w=d_w,
+                               sorted_pairs=d_pairs, T=T, topk=topk, path=q.QARL_PATH_DECODE)
+    assert norm_err_bf16(out.float().cpu().numpy(), out_ref) <= TOL_BF16
+    assert flip_fraction(np_bits(out), out_ref_bits) <= MAX_FLIPS
