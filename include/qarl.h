@@ -59,9 +59,11 @@ typedef enum { QARL_OUT_BF16 = 0, QARL_OUT_F32 = 1 } qarl_out_dtype;
  *   W4A16_G128: codes  uint32, E*N*K/8 words in 1 KiB blocks of 16 rows x 128 k (one scale group
  *                      of 16 consecutive rows), the unit a wavefront of the GEMM kernels loads:
  *                      [E*N/16 row tiles][K/128 groups][4 (k%128)/32][16 n%16][4 (k%32)/8] words;
- *                      a word holds 8 consecutive k as nibbles q+8, q in [-8,7]: element k%8 = 2i+b sits
- *                      in nibble i+4b (bits [4(i+4b), 4(i+4b)+3]), so the nibble pair (i, i+4) that one
- *                      shift-and-mask extracts is the pair of neighbours (2i, 2i+1);
+ *                      a word holds 8 consecutive k as 4-bit codes u = q+8, q in [-8,7]: elements 2i and 2i+1
+ *                      (i = 0, 1, 2) occupy bits [3+4i, 6+4i] and [19+4i, 22+4i]; element 6 bits [15, 18];
+ *                      element 7 wraps around the word: its low bit is bit 31, its upper three bits are
+ *                      bits [0, 2].  (The pair (2i, 2i+1) lands in the top mantissa bits of the two bf16
+ *                      halves of a dword after a right shift by 4i, the last pair after a rotation by 12.)
  *               scales bf16   [E][N][K/128]; dequantized weight = float(scale) * q, exact in
  *                      fp32 and never rounded to 16 bits.
  *   FP8_E4M3_CH: codes uint8  [E][N][K] (e4m3 bit patterns); scales float [E][N].

@@ -66,18 +66,24 @@ __device__ __forceinline__ uint32_t and_or_b32(uint32_t a, uint32_t mask, uint32
     return d;
 }
 
-// One packed word of eight int4 codes (element 2i+b in nibble i+4b, stored as q+8) -> eight exact
-// bf16 values (q+24)/16 in element order 0..7: the nibble lands in the top four mantissa bits of
-// bf16 1.0, and nibbles i and i+4 fall into the two halves of output dword i.  One shift and one
-// and-or per pair of codes.
+// Bit position of the low bit of element e (0..7) of a packed word of int4 codes (stored as u = q+8).
+// Elements 2i and 2i+1 (i < 3) sit 16 bits apart at bits 3+4i and 19+4i, i.e. already in the top four
+// mantissa bits of the two bf16 halves of a dword after a right shift by 4i; element 6 sits at bits
+// 15..18 and element 7 wraps around the word (its low bit at bit 31, the other three at bits 0..2), so
+// that a rotation by 12 brings both into place.
+__host__ __device__ constexpr int int4_bit_pos(int e) { return e < 6 ? 3 + 4 * (e >> 1) + 16 * (e & 1) : (e == 6 ? 15 : 31); }
+
+// One packed word of eight int4 codes -> eight exact bf16 values (q+24)/16 in element order 0..7: the
+// code lands in the top four mantissa bits of bf16 1.0.  Seven VALU operations per word: one and-or for
+// the first pair, a shift (or the rotation) and an and-or for each of the other three.
 __device__ __forceinline__ bf16x8 unpack_int4_word(uint32_t w)
 {
     const uint32_t mask = 0x00780078u, one = 0x3f803f80u;
     u32x4 d;
-    d[0] = and_or_b32(w << 3, mask, one);
-    d[1] = and_or_b32(w >> 1, mask, one);
-    d[2] = and_or_b32(w >> 5, mask, one);
-    d[3] = and_or_b32(w >> 9, mask, one);
+    d[0] = and_or_b32(w, mask, one);
+    d[1] = and_or_b32(w >> 4, mask, one);
+    d[2] = and_or_b32(w >> 8, mask, one);
+    d[3] = and_or_b32(__builtin_rotateright32(w, 12), mask, one);
     return __builtin_bit_cast(bf16x8, d);
 }
 

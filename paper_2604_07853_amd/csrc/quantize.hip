@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kQThreads) void quantize_int4_kernel(const uint16_t
     am = fmaxf(am, __shfl_xor(am, 32, 64));
     const uint32_t sb = f32_to_bf16_bits(am / 7.0f);
     const float s = bf16_bits_to_f32(sb);
-    u32x4 out = {0x88888888u, 0x88888888u, 0x88888888u, 0x88888888u};  // code 0 everywhere
+    u32x4 out = {0x44444444u, 0x44444444u, 0x44444444u, 0x44444444u};  // code 0 (u = 8) in every element
     if (s >= 0x1p-100f && s < 0x1p100f) {
         // rne(w / s) without the IEEE divide.  w and s carry 8 significant bits each and |w / s| < 8.5, so the
         // quotient either IS a half-integer or stays at least 2^-11 away from every half-integer: away from a
@@ -64,9 +64,10 @@ __global__ __launch_bounds__(kQThreads) void quantize_int4_kernel(const uint16_t
         // nibble; the constant high bits of the eight sums of a word are subtracted once at the end.
         const float rs = __builtin_amdgcn_rcpf(s);
         constexpr float kMagic = 12582912.f + 8.f;          // bit pattern 0x4B400008
-        uint32_t bias = 0;                                   // sum over the eight nibbles of 0x4B400000 << shift
+        uint32_t bias = 0;                                   // sum over the eight elements of 0x4B400000 rotated into place
 #pragma unroll
-        for (int i = 0; i < 8; ++i) bias += 0x4B400000u << (4 * ((i >> 1) + 4 * (i & 1)));
+        for (int i = 0; i < 8; ++i)
+            bias += i < 7 ? 0x4B400000u << int4_bit_pos(i) : __builtin_rotateleft32(0x4B400000u, int4_bit_pos(i));
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             uint32_t word = 0;
@@ -78,7 +79,8 @@ __global__ __launch_bounds__(kQThreads) void quantize_int4_kernel(const uint16_t
                 const float sel = fmaf(-h, s, wv) == 0.f ? h : r0;
                 // clamp first (it only bites on non-finite input; NaN -> -8), then round by the magic addition
                 const float y = __builtin_amdgcn_fmed3f(sel, -8.f, 7.f) + kMagic;
-                word += __float_as_uint(y) << (4 * ((i >> 1) + 4 * (i & 1)));  // element 2j+b -> nibble j+4b
+                // element i -> its bit position: one shift-and-add; element 7 wraps around the word (a rotation)
+                word += i < 7 ? __float_as_uint(y) << int4_bit_pos(i) : __builtin_rotateleft32(__float_as_uint(y), int4_bit_pos(i));
             }
             out[u] = word - bias;
         }
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(kQThreads) void quantize_int4_kernel(const uint16_t
             for (int i = 0; i < 8; ++i) {
                 float r = rintf(f[u * 8 + i] / s);
                 r = fminf(fmaxf(r, -8.f), 7.f);
-                word |= (uint32_t)((int)r + 8) << (4 * ((i >> 1) + 4 * (i & 1)));
+                word |= __builtin_rotateleft32((uint32_t)((int)r + 8), int4_bit_pos(i));
             }
             out[u] = word;
         }

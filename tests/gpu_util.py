@@ -62,15 +62,22 @@ def bf16_ulp_diff(a_bits, b_bits):
     return np.abs(key(np.asarray(a_bits)) - key(np.asarray(b_bits)))
 
 
+def int4_bit_pos(e):
+    """Bit position of the low bit of element e of a packed word (include/qarl.h)."""
+    return 3 + 4 * (e >> 1) + 16 * (e & 1) if e < 6 else (15 if e == 6 else 31)
+
+
 def unblock_int4(codes, E, N, K):
-    """Packed W4A16 codes as the library stores them (1 KiB blocks of 16 rows x 128 k, element 2i+b
-    of a word in nibble i+4b; see include/qarl.h) -> the oracle's packing: row-major words [E, N, K/8],
-    element i of a word in nibble i.  Pure index permutation of words and nibbles."""
+    """Packed W4A16 codes as the library stores them (1 KiB blocks of 16 rows x 128 k, the elements of a
+    word at the bit positions include/qarl.h lists, element 7 wrapping around the word) -> the oracle's
+    packing: row-major words [E, N, K/8], element i of a word in nibble i.  Pure index permutation of
+    words and bits."""
     w = np.ascontiguousarray(codes.detach().cpu().numpy()).view(np.uint32).reshape(E * N // 16, K // 128, 4, 16, 4)
     # [tile, g, q, c, i] -> [tile, c, g, q, i]
     w = np.ascontiguousarray(w.transpose(0, 3, 1, 2, 4)).reshape(E, N, K // 8)
     out = np.zeros_like(w)
     for el in range(8):
-        nib = (el >> 1) + 4 * (el & 1)
-        out |= ((w >> np.uint32(4 * nib)) & np.uint32(15)) << np.uint32(4 * el)
+        p = int4_bit_pos(el)
+        rot = (w >> np.uint32(p)) | (w << np.uint32((32 - p) % 32)) if p else w   # rotate right by p
+        out |= (rot & np.uint32(15)) << np.uint32(4 * el)
     return out
