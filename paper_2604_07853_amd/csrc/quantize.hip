@@ -160,16 +160,39 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
     const float s = am / 448.0f;
     if (lane == 0) scales[row] = s;
     u32x2 *cr = (u32x2 *)(codes + row * K);
+    // x / s, correctly rounded, without a divide per element: with y = RN(1 / s) (one IEEE divide per row),
+    // q0 = RN(x y) and the exact remainder r = x - q0 s from one FMA, RN(q0 + r y) is the correctly rounded
+    // quotient (Markstein's correction step; it needs the correctly rounded reciprocal and no underflow on the
+    // way, hence the guard on s; below 2^-11 a quotient may differ from the IEEE one, where every value rounds
+    // to an e4m3 zero; the sign is copied from x, as s > 0).  Checked against the IEEE divide for all 65536 bf16 values of x and
+    // 2^20 scales (the quantizer's own absmax / 448 and random ones): no difference at |x / s| >= 2^-11.
+    const bool fast = s >= 0x1p-100f && s < 0x1p100f && (__float_as_uint(s) & 0x7fffffu) != 0x7fffffu;
+    const float y = 1.0f / s;
+    auto div = [&](float x) -> float {
+        if (!fast) return x / s;
+        const float q0 = x * y;
+        return copysignf(fmaf(fmaf(-q0, s, x), y, q0), x);   // the sign of x also where the steps end in +0 (x = -0)
+    };
     for (int c = lane; c < n16; c += 64) {
         u32x4 v = xr[c];
         u32x2 o = {0, 0};
         if (s != 0.f) {
+            // v_cvt_pk_fp8_f32 rounds to nearest even into OCP e4m3 (subnormals included) exactly like
+            // e4m3_from_f32 for every finite |t| <= 448 (checked over all 2^32 bit patterns on gfx950); the
+            // clamp keeps the quotient of the row's absmax, which may exceed 448 by an ulp, in that range
+            // (and sends a NaN to -448).
+            float t[8];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                uint32_t lo = e4m3_from_f32(__uint_as_float(v[i] << 16) / s);
-                uint32_t hi = e4m3_from_f32(__uint_as_float(v[i] & 0xffff0000u) / s);
-                o[i >> 1] |= (lo | (hi << 8)) << (16 * (i & 1));
+                t[2 * i] = __builtin_amdgcn_fmed3f(div(__uint_as_float(v[i] << 16)), -448.f, 448.f);
+                t[2 * i + 1] = __builtin_amdgcn_fmed3f(div(__uint_as_float(v[i] & 0xffff0000u)), -448.f, 448.f);
             }
+            int w0 = __builtin_amdgcn_cvt_pk_fp8_f32(t[0], t[1], 0, false);
+            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(t[2], t[3], w0, true);
+            int w1 = __builtin_amdgcn_cvt_pk_fp8_f32(t[4], t[5], 0, false);
+            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(t[6], t[7], w1, true);
+            o[0] = (uint32_t)w0;
+            o[1] = (uint32_t)w1;
         }
         cr[c] = o;
     }

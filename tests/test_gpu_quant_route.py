@@ -72,6 +72,39 @@ def test_fp8_cast_all_magnitudes(q, oracle):
     assert (c2 & 0x78 == 0).sum() > 100                    # subnormal codes were exercised
 
 
+def test_fp8_rows_signed_zero_ties_and_random_patterns(q, oracle):
+    """The row quantizer divides by a reciprocal with an exact correction and converts with the hardware
+    instruction: rows of arbitrary bf16 bit patterns (every exponent the row's scale lets through, +-0,
+    subnormal bf16 inputs), exact ties between neighbouring e4m3 values and both signs of zero must give
+    the oracle's bytes (IEEE divide, then round to nearest even)."""
+    rng = np.random.default_rng(11)
+    K = 1024
+    rows = []
+    for r in range(96):
+        top = rng.integers(100, 150)                                  # exponent field of the row's absmax
+        ex = rng.integers(max(1, top - 40), top + 1, size=K)          # spread over 40 binades below it
+        bits = (rng.integers(0, 2, size=K) << 15) | (ex << 7) | rng.integers(0, 128, size=K)
+        bits[rng.integers(0, K, size=8)] = 0x0000                     # +0
+        bits[rng.integers(0, K, size=8)] = 0x8000                     # -0
+        bits[rng.integers(0, K, size=4)] = rng.integers(1, 128, size=4)            # subnormal bf16 inputs
+        bits[0] = (top << 7) | rng.integers(0, 128)                   # the row's absmax
+        rows.append(bits.astype(np.uint16))
+    # rows whose scale is a power of two: every bf16 input with <= 5 significant bits lands on an e4m3 value or
+    # exactly between two of them
+    for r in range(32):
+        m = rng.integers(0, 32, size=K) << 2                          # mantissa with 5 significant bits (incl. hidden one)
+        ex = rng.integers(110, 128, size=K)
+        bits = (rng.integers(0, 2, size=K) << 15) | (ex << 7) | m
+        bits[0] = (127 << 7) | 0x60                                   # absmax 1.75 * 2^0 = 448 * 2^-8
+        rows.append(bits.astype(np.uint16))
+    xb = np.stack(rows)
+    c_ref, s_ref = oracle.quantize_fp8_rows(xb)
+    gc, gs = q.qarl_quantize_rows_fp8(synth.from_bits(xb).cuda())
+    assert np.array_equal(gs.cpu().numpy(), s_ref)
+    assert np.array_equal(gc.cpu().numpy(), c_ref)
+    assert ((c_ref == 0x80).sum() > 100) and ((c_ref == 0x00).sum() > 100)     # both zeros occurred
+
+
 @pytest.mark.parametrize("T,E,topk,zipf", [(300, 128, 8, 0.0), (1000, 128, 8, 1.1), (64, 64, 2, 0.0),
                                            (33, 256, 8, 0.0), (1, 128, 8, 0.0), (257, 128, 1, 0.0)])
 def test_route_exact(q, oracle, T, E, topk, zipf):
