@@ -106,6 +106,18 @@ __global__ __launch_bounds__(kLThreads, 2) void lmhead_lse_kernel(LogprobParams 
             for (int nt = 0; nt < 2; ++nt)
                 acc[ms][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ms], f.b[nt], acc[ms][nt], 0, 0, 0);
     };
+    // Issue order of a slice: one MFMA, then the six operand reads of the next slice one by one between the
+    // next six MFMAs (an LDS read every 32 cycles instead of six at once; 3 % faster than all six behind
+    // the first MFMA), then the last MFMA.
+    auto interleave = [&]() {
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
     auto stage_barrier = [&]() {
         // own copies landed, own operand reads done; then everybody's
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -127,30 +139,16 @@ __global__ __launch_bounds__(kLThreads, 2) void lmhead_lse_kernel(LogprobParams 
         if (ks + 1 < stages) copy_stage(ks + 1, buf ^ 1);
         read_frags(f0, buf, 0);
         mfma8(last);
-        // one MFMA, the six operand reads of the next slice, the other seven MFMAs: the wait in front of
-        // a slice then finds only reads issued seven MFMAs earlier
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave();
         read_frags(f1, buf, 1);
         mfma8(f0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave();
         read_frags(f2, buf, 2);
         mfma8(f1);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave();
         read_frags(f3, buf, 3);
         mfma8(f2);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave();
         stage_barrier();
         last = f3;
     }
