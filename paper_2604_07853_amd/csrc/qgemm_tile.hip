@@ -260,47 +260,93 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
         lds_barrier();
     }
 
-    // ---- epilogue: lane (c,h), register i -> token row 8*(i/4) + 4h + i%4, column c of the tile
+    // ---- epilogue: lane (c,h), register i -> token row 8*(i/4) + 4h + i%4, column c of the tile.
+    // A lane holds one column of 16 rows, so a direct store would move 4 (or 2) bytes per lane.  The results
+    // take a turn through the activation buffers, which are free after the loop's last barrier, and leave as
+    // 16-byte pieces of whole 128-byte row segments.
     const float swn = kInt4 ? 1.f : ((const float *)p.scales)[wr];
-    const int ncols = kSilu ? N / 2 : N;
-    const int esz = (kSilu || !p.out_f32) ? 2 : 4;
-    unsigned char *obase = (unsigned char *)p.out + (int64_t)ocol * esz;
-    const uint32_t rstride = (uint32_t)ncols * (uint32_t)esz;   // bytes per output row (< 2^31: checked by the launcher)
+    static_assert(2 * kBufBytes >= kBM * (kBN / 2) * 2 && 2 * kBufBytes >= (kThreads / 64) * 32 * 32 * 4, "epilogue tile does not fit");
+    if (kSilu) {
+        // workgroup tile [kBM rows][128 columns] bf16 in LDS
+        uint16_t *ot = (uint16_t *)smem;
 #pragma unroll
-    for (int ms = 0; ms < MS; ++ms) {
+        for (int ms = 0; ms < MS; ++ms) {
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-            const i32x4 orow4 = *(const i32x4 *)(s_orow + ms * 32 + 8 * i4 + 4 * h);
-            f32x4 vv;
+            for (int i4 = 0; i4 < 4; ++i4) {
+                f32x4 vv;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) vv[i] = acc[ms][i4 * 4 + i];
-            if (!kInt4) {
-                const f32x4 xs4 = *(const f32x4 *)(s_xs + ms * 32 + 8 * i4 + 4 * h);
+                for (int i = 0; i < 4; ++i) vv[i] = acc[ms][i4 * 4 + i];
+                if (!kInt4) {
+                    const f32x4 xs4 = *(const f32x4 *)(s_xs + ms * 32 + 8 * i4 + 4 * h);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) vv[i] *= xs4[i] * swn;
-            }
-            if (kSilu) {
+                    for (int i = 0; i < 4; ++i) vv[i] *= xs4[i] * swn;
+                }
                 // Registers i and i+1 trade 16-lane rows: afterwards every lane holds a gate value
                 // and the up value of the same column; lanes c < 16 for row i, lanes c >= 16 for row i+1.
 #pragma unroll
                 for (int ip = 0; ip < 2; ++ip) {
                     const u32x2 sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(vv[2 * ip]),
                                                                       __float_as_uint(vv[2 * ip + 1]), false, false);
-                    const int orow = c < 16 ? orow4[2 * ip] : orow4[2 * ip + 1];
-                    if (orow >= 0 && tile_ok) {
-                        const float a = silu_mul_f32(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-                        *(uint16_t *)(obase + (uint64_t)(uint32_t)orow * rstride) = f32_to_bf16_hw(a);
-                    }
+                    const int row = ms * 32 + 8 * i4 + 4 * h + 2 * ip + (c >> 4);
+                    const float a = silu_mul_f32(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                    ot[row * (kBN / 2) + wn * 16 + (c & 15)] = f32_to_bf16_hw(a);
                 }
-            } else {
+            }
+        }
+        lds_barrier();
+        constexpr int kPieces = kBM * (kBN / 2) * 2 / 16;   // 16 pieces per row
+        const uint32_t rstride = (uint32_t)(N / 2) * 2u;    // bytes per output row (< 2^31: checked by the launcher)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (orow4[i] >= 0 && tile_ok) {
-                        if (p.out_f32) __builtin_nontemporal_store(vv[i], (float *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride));
-                        else __builtin_nontemporal_store(f32_to_bf16_hw(vv[i]), (uint16_t *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride));
+        for (int q0 = 0; q0 < kPieces; q0 += kThreads) {
+            const int q = q0 + tid, row = q >> 4, piece = q & 15;
+            const int orow = s_orow[row];
+            const int oc = nb * (kBN / 2) + piece * 8;
+            const u32x4 v4 = *(const u32x4 *)(ot + row * (kBN / 2) + piece * 8);
+            if (orow >= 0 && oc + 8 <= N / 2)
+                *(u32x4 *)((unsigned char *)p.out + ((uint64_t)(uint32_t)orow * rstride + (uint32_t)oc * 2u)) = v4;
+        }
+    } else {
+        // per wavefront [32 rows][32 columns] fp32 in LDS, one 32-row tile after the other; only the wavefront
+        // itself touches its region, and the LDS operations of a wavefront execute in order
+        float *ot = (float *)smem + wn * (32 * 32);
+        const int esz = p.out_f32 ? 4 : 2;
+        const uint32_t rstride = (uint32_t)N * (uint32_t)esz;   // bytes per output row (< 2^31: checked by the launcher)
+        const int oc = nb * kBN + wn * 32 + (lane & 7) * 4;      // first of this lane's four columns
+        unsigned char *obase = (unsigned char *)p.out + (int64_t)oc * esz;
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms) {
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                f32x4 vv;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) vv[i] = acc[ms][i4 * 4 + i];
+                if (!kInt4) {
+                    const f32x4 xs4 = *(const f32x4 *)(s_xs + ms * 32 + 8 * i4 + 4 * h);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) vv[i] *= xs4[i] * swn;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ot[(8 * i4 + 4 * h + i) * 32 + c] = vv[i];
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
+                const int row = pass * 8 + (lane >> 3);
+                const f32x4 v4 = *(const f32x4 *)(ot + row * 32 + (lane & 7) * 4);
+                const int orow = s_orow[ms * 32 + row];
+                if (orow >= 0 && tile_ok) {
+                    unsigned char *dst = obase + (uint64_t)(uint32_t)orow * rstride;
+                    if (p.out_f32) {
+                        __builtin_nontemporal_store(v4, (f32x4 *)dst);
+                    } else {
+                        u32x2 o;
+                        o[0] = (uint32_t)f32_to_bf16_hw(v4[0]) | ((uint32_t)f32_to_bf16_hw(v4[1]) << 16);
+                        o[1] = (uint32_t)f32_to_bf16_hw(v4[2]) | ((uint32_t)f32_to_bf16_hw(v4[3]) << 16);
+                        __builtin_nontemporal_store(o, (u32x2 *)dst);
                     }
                 }
             }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
     }
 }

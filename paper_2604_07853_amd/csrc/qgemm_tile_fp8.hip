@@ -4,7 +4,10 @@
 //
 // Both operands are MFMA inputs as stored, so the kernel is a plain dense contraction: a workgroup owns
 // 128 token rows x 256 weight rows of one expert; its eight wavefronts (2 x 4) own 64 x 64 each as 2 x 2
-// v_mfma_f32_32x32x64_f8f6f4 tiles (e4m3 x e4m3, unit block scales).  Token rows (gathered through row_map) and weight rows reach LDS by
+// v_mfma_f32_32x32x64_f8f6f4 tiles (e4m3 x e4m3, unit block scales).  The weight rows are the MFMA's row
+// operand and the tokens its column operand, so a lane ends up with four consecutive output columns of ONE
+// token per register quad: results leave in 16-byte (fp32) or 8-byte (bf16) stores, and the gate and up value
+// of a column meet in the same lane.  Token rows (gathered through row_map) and weight rows reach LDS by
 // asynchronous global -> LDS copies, three 128-k stages deep; 16-byte chunks of a row are XOR-swizzled with
 // the row index so that the copies (8 rows x 128 bytes per wavefront instruction) and the operand reads
 // (32 rows, one chunk) are free of bank conflicts.  The operand reads of half a stage run under the MFMAs
@@ -44,6 +47,7 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
     __shared__ __attribute__((aligned(16))) int s_rows[kFTM];
     __shared__ __attribute__((aligned(16))) int s_orow[kFTM];
     __shared__ __attribute__((aligned(16))) float s_xs[kFTM];
+    __shared__ __attribute__((aligned(16))) float s_wn[2][kFTN];   // channel scale of every LDS weight row, per column block parity
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 2, wn = wave & 3;
@@ -128,6 +132,7 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
         const int q = (lane & 7) ^ ((r >> 1) & 7);
         aptr[i] = p.x + (int64_t)s_rows[r] * K + q * 16;
     }
+    uint32_t soff = 0;   // weight row whose scale this lane copies: LDS row 64 (wave % 4) + lane
     auto set_block = [&](int nb) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -135,9 +140,11 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
             const int q = (lane & 7) ^ ((r >> 1) & 7);
             boff[i] = (uint32_t)weight_row(nb, r) * (uint32_t)K + q * 16;
         }
+        soff = (uint32_t)weight_row(nb, (wave & 3) * 64 + lane);
     };
     set_block(nb0);
     const unsigned char *wbase = p.codes + (int64_t)e * N * K;
+    const float *sbase = p.scales + (int64_t)e * N;
     auto copy_stage = [&](int ks, int buf) {
         unsigned char *dst = smem + buf * kFStageB;
 #pragma unroll
@@ -185,7 +192,7 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
         for (int ms = 0; ms < 2; ++ms)
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)   // e4m3 x e4m3, no block scales
-                acc[ms][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.a[ms], f.b[nt], acc[ms][nt], 0, 0, 0, 0, 0, 0);
+                acc[ms][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.b[nt], f.a[ms], acc[ms][nt], 0, 0, 0, 0, 0, 0);
     };
 
     // Rotated loop (see logprob.hip): the MFMAs of a stage's last group run in the next trip, behind the
@@ -199,11 +206,16 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
         last.a[i] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
         last.b[i] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
-    auto start_block = [&]() {   // first two stages of a column block into buffers 0 and 1
+    // First two stages of a column block into buffers 0 and 1; in front of them the block's 256 channel
+    // scales, 4 bytes per lane (wavefronts w and w + 4 copy the same 64), into the half of s_wn the block's
+    // parity selects.  They are older than every stage copy, so each counted wait below covers them.
+    auto start_block = [&](int par) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(sbase + soff),
+                                         (__attribute__((address_space(3))) void *)(&s_wn[par][(wave & 3) * 64]), 4, 0, 0);
         copy_stage(0, 0);
         if (stages > 1) copy_stage(1, 1);
     };
-    start_block();
+    start_block(0);
   for (int bi = 0; bi < p.bpw && nb0 + bi < p.n_blocks; ++bi) {
     const int nb = nb0 + bi;
     if (stages > 1)
@@ -246,62 +258,68 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
         last.b[i] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
 
-    // ---- epilogue: lane (c,h), register i -> token row 64 wm + 32 ms + 8 (i/4) + 4 h + i%4, column c of tile nt.
+    // ---- epilogue: lane (c,h), register i of acc[ms][nt] -> token row 64 wm + 32 ms + c, LDS weight row
+    // 64 wn + 32 nt + 8 (i/4) + 4 h + i%4: four consecutive rows, i.e. output columns, per register quad.
     // The first copies of the next column block are issued first (every buffer is free after the last
     // barrier), so they travel while this block's results are scaled and stored.
-    float swn2[2];
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) swn2[nt] = p.scales[(int64_t)e * N + weight_row(nb, wn * 64 + nt * 32 + c)];
     if (bi + 1 < p.bpw && nb + 1 < p.n_blocks) {
         set_block(nb + 1);
-        start_block();
+        start_block((bi + 1) & 1);
     }
+    const float *wsc = s_wn[bi & 1];
     const int ncols = kSilu ? N / 2 : N;
     const int esz = (kSilu || !p.out_f32) ? 2 : 4;
     const uint32_t rstride = (uint32_t)ncols * (uint32_t)esz;
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int rho = wn * 64 + nt * 32 + c;
-        int ocol;
-        bool tile_ok;
-        if (kSilu) {
-            ocol = nb * (kFTN / 2) + (rho >> 5) * 16 + (rho & 15);
-            tile_ok = ocol - (rho & 15) + 16 <= N / 2;
-        } else {
-            ocol = nb * kFTN + rho;
-            tile_ok = ocol - (rho & 31) + 32 <= N;
-        }
-        const float swn = swn2[nt];
-        unsigned char *obase = (unsigned char *)p.out + (int64_t)ocol * esz;
+    for (int ms = 0; ms < 2; ++ms) {
+        const int trow = wm * 64 + ms * 32 + c;
+        const int orow = s_orow[trow];
+        const float xs = s_xs[trow];
+        unsigned char *orow_base = (unsigned char *)p.out + (uint64_t)(uint32_t)max(orow, 0) * rstride;
 #pragma unroll
-        for (int ms = 0; ms < 2; ++ms) {
+        for (int nt = 0; nt < 2; ++nt) {
+            const int rho0 = wn * 64 + nt * 32;
+            if (kSilu) {
+                // rows rho0 .. +15 are gate rows, rho0 + 16 .. +31 the matching up rows: registers i and i + 8
+                const int ocol0 = nb * (kFTN / 2) + (rho0 >> 5) * 16;
+                const bool tile_ok = ocol0 + 16 <= N / 2;
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const int rbase = wm * 64 + ms * 32 + 8 * i4 + 4 * h;
-                const i32x4 orow4 = *(const i32x4 *)(s_orow + rbase);
-                const f32x4 xs4 = *(const f32x4 *)(s_xs + rbase);
-                f32x4 vv;
+                for (int a4 = 0; a4 < 2; ++a4) {
+                    const int r = 8 * a4 + 4 * h;
+                    const f32x4 sg = *(const f32x4 *)(wsc + rho0 + r), su = *(const f32x4 *)(wsc + rho0 + 16 + r);
+                    u32x2 o;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) vv[i] = acc[ms][nt][i4 * 4 + i] * (xs4[i] * swn);
-                if (kSilu) {
-                    // registers i and i+1 trade 16-lane rows: every lane then holds a gate value and the up
-                    // value of the same column; lanes c < 16 for row i, lanes c >= 16 for row i+1
+                    for (int b2 = 0; b2 < 2; ++b2) {
+                        uint32_t pk = 0;
 #pragma unroll
-                    for (int ip = 0; ip < 2; ++ip) {
-                        const u32x2 sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(vv[2 * ip]),
-                                                                          __float_as_uint(vv[2 * ip + 1]), false, false);
-                        const int orow = (c & 16) ? orow4[2 * ip + 1] : orow4[2 * ip];
-                        if (orow >= 0 && tile_ok) {
-                            const float a = silu_mul_f32(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-                            *(uint16_t *)(obase + (uint64_t)(uint32_t)orow * rstride) = f32_to_bf16_hw(a);
+                        for (int q = 0; q < 2; ++q) {
+                            const int i = 2 * b2 + q;
+                            const float g = acc[ms][nt][4 * a4 + i] * (xs * sg[i]);
+                            const float u = acc[ms][nt][8 + 4 * a4 + i] * (xs * su[i]);
+                            pk |= (uint32_t)f32_to_bf16_hw(silu_mul_f32(g, u)) << (16 * q);
                         }
+                        o[b2] = pk;
                     }
-                } else {
+                    if (orow >= 0 && tile_ok) *(u32x2 *)(orow_base + (ocol0 + r) * 2) = o;
+                }
+            } else {
+                const int ocol0 = nb * kFTN + rho0;
+                const bool tile_ok = ocol0 + 32 <= N;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        if (orow4[i] >= 0 && tile_ok) {
-                            if (p.out_f32) __builtin_nontemporal_store(vv[i], (float *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride));
-                            else __builtin_nontemporal_store(f32_to_bf16_hw(vv[i]), (uint16_t *)(obase + (uint64_t)(uint32_t)orow4[i] * rstride));
+                for (int a4 = 0; a4 < 4; ++a4) {
+                    const int r = 8 * a4 + 4 * h;
+                    const f32x4 sw = *(const f32x4 *)(wsc + rho0 + r);
+                    f32x4 vv;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) vv[i] = acc[ms][nt][4 * a4 + i] * (xs * sw[i]);
+                    if (orow >= 0 && tile_ok) {
+                        if (p.out_f32) {
+                            *(f32x4 *)(orow_base + (ocol0 + r) * 4) = vv;
+                        } else {
+                            u32x2 o;
+                            o[0] = (uint32_t)f32_to_bf16_hw(vv[0]) | ((uint32_t)f32_to_bf16_hw(vv[1]) << 16);
+                            o[1] = (uint32_t)f32_to_bf16_hw(vv[2]) | ((uint32_t)f32_to_bf16_hw(vv[3]) << 16);
+                            *(u32x2 *)(orow_base + (ocol0 + r) * 2) = o;
                         }
                     }
                 }
