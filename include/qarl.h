@@ -108,7 +108,8 @@ int qarl_quantize_rows_fp8(const void *x_bf16, int64_t rows, int K, void *codes,
  * sorted_tokens[i] = sorted_pairs[i] / topk.  Section 4.1 names the router as where
  * quantized MoE rollouts drift, so ids and grouping are exact integer work.
  * Supported: E % 64 == 0, E <= 256, 1 <= topk <= min(E, 32).  T == 0 is a no-op that
- * still writes zero counts and offsets. */
+ * still writes zero counts and offsets.  With all four grouping outputs NULL only topk_ids and
+ * topk_w are written (what qarl_qgemm_routed consumes). */
 int qarl_moe_route(const void *logits_bf16, int T, int E, int topk, int renorm, int32_t *topk_ids,
                    float *topk_w, int32_t *expert_counts, int32_t *expert_offsets,
                    int32_t *sorted_pairs, int32_t *sorted_tokens, void *stream);
@@ -135,6 +136,25 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
                        int epilogue, const float *combine_w, const int32_t *sorted_pairs, int T,
                        int topk, void *out, int out_dtype, int path, void *ws, size_t ws_bytes,
                        void *stream);
+
+/* The same contraction driven by the router's ids directly, for decode-sized batches (section 4.1's
+ * rollout regime: a few hundred tokens over all experts), so that no grouping pass sits between the
+ * router and the expert GEMMs: problem row pr = t*topk + slot, pr in [0, T*topk), multiplies expert
+ * topk_ids[pr].  It reads activation row t (x_per_token != 0: x is bf16 [T][K]) or row pr (x is bf16
+ * [T*topk][K]) and writes output row pr; every workgroup lists its expert's rows itself, in increasing
+ * pr, which is the (expert, token, slot) order of qarl_moe_route's grouping.
+ *   epilogue   NONE: out [T*topk][N];  SILU_MUL: out bf16 [T*topk][N/2];
+ *              COMBINE: Y staged in ws as fp32 [T*topk][N] (qarl_qgemm_workspace_bytes with M = T*topk),
+ *              out [T][N] = sum over slots of combine_w[t][slot] * Y[t*topk + slot], in slot order
+ * Results equal those of qarl_qgemm_grouped on the DECODE path with the grouping of the same ids, bit
+ * for bit (same kernels, same order of operations per row).
+ * Supported: W4A16_G128 with the DECODE path's shapes (N % 32 == 0, K % 256 == 0, K <= 2048), T <= 512,
+ * T*topk <= 4096, a token listing an expert at most once (as the router's output does; rows past 512 of
+ * one expert would be dropped); ids outside [0, E) select no expert and leave their output rows
+ * unwritten.  topk_ids 16-byte aligned.  Errors as for qarl_qgemm_grouped.  T == 0 is a no-op. */
+int qarl_qgemm_routed(const qarl_qweight *W, const void *x, int x_per_token, const int32_t *topk_ids,
+                      int T, int topk, int epilogue, const float *combine_w, void *out, int out_dtype,
+                      void *ws, size_t ws_bytes, void *stream);
 
 /* LM head fused with the per-token log-prob: z = inv_temperature * h W_lm^T (bf16 inputs,
  * fp32 accumulation, logits never stored), logprob[t] = z[t][target[t]] - logsumexp_v z[t][v].

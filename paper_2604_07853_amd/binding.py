@@ -22,7 +22,7 @@ QARL_OUT_BF16, QARL_OUT_F32 = 0, 1
 
 EXPORTS = ["qarl_last_error", "qarl_qgemm_workspace_bytes", "qarl_logprob_workspace_bytes",
            "qarl_quantize_weights", "qarl_quantize_rows_fp8", "qarl_moe_route", "qarl_qgemm_grouped",
-           "qarl_token_logprob", "qarl_logprob_mismatch"]
+           "qarl_qgemm_routed", "qarl_token_logprob", "qarl_logprob_mismatch"]
 
 
 class QarlError(RuntimeError):
@@ -58,6 +58,8 @@ def lib():
         L.qarl_qgemm_grouped.argtypes = [C.POINTER(qarl_qweight), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                          C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                          C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.qarl_qgemm_routed.argtypes = [C.POINTER(qarl_qweight), C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                        C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
         L.qarl_token_logprob.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -138,12 +140,17 @@ class Routing:
         self.tokens = torch.empty((T * topk,), **i32)
 
 
-def qarl_moe_route(logits, topk=8, renorm=True, out=None):
+def qarl_moe_route(logits, topk=8, renorm=True, out=None, group=True):
+    """group=False: ids and weights only (the grouping outputs of `out` keep their old contents)."""
     assert logits.dtype == torch.bfloat16 and logits.is_cuda and logits.is_contiguous() and logits.dim() == 2
     T, E = logits.shape
     r = out if out is not None else Routing(T, E, topk, logits.device)
-    _check(lib().qarl_moe_route(_ptr(logits), T, E, topk, int(renorm), _ptr(r.ids), _ptr(r.w), _ptr(r.counts),
-                                _ptr(r.offsets), _ptr(r.pairs), _ptr(r.tokens), _stream()))
+    if group:
+        _check(lib().qarl_moe_route(_ptr(logits), T, E, topk, int(renorm), _ptr(r.ids), _ptr(r.w), _ptr(r.counts),
+                                    _ptr(r.offsets), _ptr(r.pairs), _ptr(r.tokens), _stream()))
+    else:
+        _check(lib().qarl_moe_route(_ptr(logits), T, E, topk, int(renorm), _ptr(r.ids), _ptr(r.w), None, None, None,
+                                    None, _stream()))
     return r
 
 
@@ -172,6 +179,28 @@ def qarl_qgemm_grouped(W, x, expert_offsets, M, row_map=None, x_scales=None, epi
     _check(lib().qarl_qgemm_grouped(C.byref(W.desc), _ptr(x), _ptr(x_scales), x.shape[0], _ptr(row_map),
                                     _ptr(expert_offsets), M, epilogue, _ptr(combine_w), _ptr(sorted_pairs), T, topk,
                                     _ptr(out), out_dtype, path, _ptr(ws), ws_bytes, _stream()))
+    return out
+
+
+def qarl_qgemm_routed(W, x, topk_ids, T, topk, x_per_token, epilogue=QARL_EPI_NONE, combine_w=None, out=None,
+                      out_dtype=QARL_OUT_BF16, ws=None):
+    """Grouped quantized GEMM driven by the router's ids; see include/qarl.h.  Allocates `out` / `ws` when not given."""
+    dev = x.device
+    N, M = W.N, T * topk
+    if out is None:
+        dt = torch.float32 if out_dtype == QARL_OUT_F32 else torch.bfloat16
+        if epilogue == QARL_EPI_COMBINE:
+            out = torch.empty((T, N), dtype=dt, device=dev)
+        elif epilogue == QARL_EPI_SILU_MUL:
+            out = torch.empty((M, N // 2), dtype=dt, device=dev)
+        else:
+            out = torch.empty((M, N), dtype=dt, device=dev)
+    need = qarl_qgemm_workspace_bytes(W, x.shape[0], M, epilogue)
+    if ws is None and need:
+        ws = torch.empty((need,), dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(lib().qarl_qgemm_routed(C.byref(W.desc), _ptr(x), int(bool(x_per_token)), _ptr(topk_ids), T, topk, epilogue,
+                                   _ptr(combine_w), _ptr(out), out_dtype, _ptr(ws), ws_bytes, _stream()))
     return out
 
 
@@ -216,9 +245,12 @@ class MoELayer:
     """One quantized MoE FFN layer driven through the C ABI: route -> gate_up (SiLU*mul) -> down (combine).
     Holds the preallocated intermediates so a step launches kernels only."""
 
-    def __init__(self, gate_up: QWeight, down: QWeight, T, topk=8, path=QARL_PATH_AUTO, device="cuda"):
+    def __init__(self, gate_up: QWeight, down: QWeight, T, topk=8, path=QARL_PATH_AUTO, device="cuda", routed=None):
         self.gu, self.dn, self.T, self.topk, self.path = gate_up, down, T, topk, path
         self.fp8 = gate_up.fmt == QARL_FP8_E4M3_CH
+        # decode-sized W4A16 batches skip the grouping pass: the GEMMs read the router's ids themselves
+        self.routed = (routed if routed is not None else
+                       (not self.fp8 and path == QARL_PATH_DECODE and 0 < T <= 512 and T * topk <= 4096))
         E, I, H = gate_up.E, gate_up.N // 2, gate_up.K
         self.E, self.I, self.H = E, I, H
         M = T * topk
@@ -236,6 +268,13 @@ class MoELayer:
             self.sa = torch.empty((M,), dtype=torch.float32, device=device)
 
     def forward(self, x, logits):
+        if self.routed:
+            r = qarl_moe_route(logits, self.topk, True, out=self.routing, group=False)
+            qarl_qgemm_routed(self.gu, x, r.ids, self.T, self.topk, True, epilogue=QARL_EPI_SILU_MUL, out=self.a,
+                              ws=self.ws)
+            qarl_qgemm_routed(self.dn, self.a, r.ids, self.T, self.topk, False, epilogue=QARL_EPI_COMBINE,
+                              combine_w=r.w, out=self.out, ws=self.ws)
+            return self.out
         r = qarl_moe_route(logits, self.topk, True, out=self.routing)
         if self.fp8:
             qarl_quantize_rows_fp8(x, self.xq, self.sx)

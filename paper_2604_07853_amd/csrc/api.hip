@@ -146,6 +146,15 @@ int qarl_moe_route(const void *logits_bf16, int T, int E, int topk, int renorm, 
         set_error("qarl_moe_route: T*topk overflows int32");
         return QARL_ERR_UNSUPPORTED;
     }
+    const bool no_grouping = !expert_counts && !expert_offsets && !sorted_pairs && !sorted_tokens;
+    if (no_grouping) {   // ids and weights only (for qarl_qgemm_routed)
+        if (T == 0) return QARL_OK;
+        if (!logits_bf16 || !topk_ids || !topk_w) {
+            set_error("qarl_moe_route: null pointer");
+            return QARL_ERR_INVALID_ARG;
+        }
+        return launch_route_only(logits_bf16, T, E, topk, renorm, topk_ids, topk_w, (hipStream_t)stream);
+    }
     if (!expert_counts || !expert_offsets || (T > 0 && (!logits_bf16 || !topk_ids || !topk_w || !sorted_pairs || !sorted_tokens))) {
         set_error("qarl_moe_route: null pointer");
         return QARL_ERR_INVALID_ARG;
@@ -253,6 +262,90 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
         a.x_group_sums = gs;
     }
     rc = (use == QARL_PATH_DECODE) ? launch_qgemm_stream(a, st) : launch_qgemm_tile(a, st);
+    if (rc) return rc;
+    if (epilogue == QARL_EPI_COMBINE)
+        return launch_combine((const float *)ws, combine_w, T, topk, W->N, out, out_dtype == QARL_OUT_F32, st);
+    return QARL_OK;
+}
+
+int qarl_qgemm_routed(const qarl_qweight *W, const void *x, int x_per_token, const int32_t *topk_ids, int T,
+                      int topk, int epilogue, const float *combine_w, void *out, int out_dtype, void *ws,
+                      size_t ws_bytes, void *stream)
+{
+    int rc = check_qweight(W, "qarl_qgemm_routed");
+    if (rc) return rc;
+    if (T < 0 || topk <= 0) {
+        set_error("qarl_qgemm_routed: T >= 0 and topk > 0 required");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (epilogue != QARL_EPI_NONE && epilogue != QARL_EPI_SILU_MUL && epilogue != QARL_EPI_COMBINE) {
+        set_error("qarl_qgemm_routed: unknown epilogue %d", epilogue);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (out_dtype != QARL_OUT_BF16 && out_dtype != QARL_OUT_F32) {
+        set_error("qarl_qgemm_routed: unknown out_dtype %d", out_dtype);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (epilogue == QARL_EPI_SILU_MUL && out_dtype != QARL_OUT_BF16) {
+        set_error("qarl_qgemm_routed: SILU_MUL needs bf16 output");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (epilogue == QARL_EPI_COMBINE && W->N % 4 != 0) {
+        set_error("qarl_qgemm_routed: COMBINE needs N %% 4 == 0");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (T == 0) return QARL_OK;
+    if (W->fmt != QARL_W4A16_G128 || !qgemm_stream_w4_routed_supported(W->N, W->K, T, topk)) {
+        set_error("qarl_qgemm_routed: supports W4A16 in the DECODE path's shapes (N %% 32 == 0, K %% 256 == 0, K <= 2048), "
+                  "T <= 512 and T * topk <= 4096 (got fmt=%d N=%d K=%d T=%d topk=%d)", W->fmt, W->N, W->K, T, topk);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (!x || !topk_ids || !out) {
+        set_error("qarl_qgemm_routed: null pointer");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!aligned16(x) || !aligned16(out) || !aligned16(topk_ids)) {
+        set_error("qarl_qgemm_routed: x, topk_ids and out must be 16-byte aligned");
+        return QARL_ERR_ALIGNMENT;
+    }
+    const int64_t M = (int64_t)T * topk;
+    GemmArgs a;
+    a.fmt = W->fmt;
+    a.E = W->E;
+    a.N = W->N;
+    a.K = W->K;
+    a.codes = W->codes;
+    a.scales = W->scales;
+    a.x = x;
+    a.x_scales = nullptr;
+    a.row_map = nullptr;
+    a.out_row_map = nullptr;
+    a.offsets = nullptr;
+    a.M = M;
+    a.x_rows = x_per_token ? T : M;
+    a.epilogue = epilogue;
+    a.out = out;
+    a.out_f32 = (out_dtype == QARL_OUT_F32);
+    a.x_group_sums = nullptr;
+    a.ids = topk_ids;
+    a.topk = topk;
+    a.x_per_token = x_per_token ? 1 : 0;
+    const size_t stage = ws_stage_bytes(W, M, epilogue);
+    if (stage > 0 && (!ws || ws_bytes < stage || !aligned16(ws))) {
+        set_error("qarl_qgemm_routed: this call needs %zu bytes of 16-byte aligned workspace (got %zu)", stage, ws_bytes);
+        return QARL_ERR_WORKSPACE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (epilogue == QARL_EPI_COMBINE) {
+        if (!combine_w) {
+            set_error("qarl_qgemm_routed: COMBINE needs combine_w");
+            return QARL_ERR_INVALID_ARG;
+        }
+        a.epilogue = QARL_EPI_NONE;
+        a.out = ws;
+        a.out_f32 = 1;
+    }
+    rc = launch_qgemm_stream_w4(a, st);
     if (rc) return rc;
     if (epilogue == QARL_EPI_COMBINE)
         return launch_combine((const float *)ws, combine_w, T, topk, W->N, out, out_dtype == QARL_OUT_F32, st);

@@ -118,6 +118,7 @@ int check_hip(hipError_t e, const char *what);
 // Kernel launchers (one per .hip file); all validate nothing: api.hip does.
 int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *scales, hipStream_t s);
 int launch_quantize_fp8_rows(const void *x, int64_t rows, int K, void *codes, float *scales, hipStream_t s);
+int launch_route_only(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w, hipStream_t s);
 int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w,
                  int32_t *counts, int32_t *offsets, int32_t *pairs, int32_t *tokens, hipStream_t s);
 
@@ -137,11 +138,17 @@ struct GemmArgs {
     int epilogue;       // NONE or SILU_MUL here; COMBINE is NONE into ws + combine kernel
     void *out;          // [M][N] or [M][N/2]
     int out_f32;
+    // routed mode of the W4A16 decode kernel (ids != null; offsets and row maps unused): row = pair id
+    // t * topk + slot of expert ids[row], activation row t (x_per_token) or the pair id, output row = pair id
+    const int32_t *ids = nullptr;
+    int topk = 0;
+    int x_per_token = 0;
 };
 int launch_qgemm_stream(const GemmArgs &a, hipStream_t s);
 bool qgemm_stream_supported(int fmt, int N, int K);
 int launch_qgemm_stream_w4(const GemmArgs &a, hipStream_t s);
 bool qgemm_stream_w4_supported(int N, int K);
+bool qgemm_stream_w4_routed_supported(int N, int K, int T, int topk);
 int launch_qgemm_tile(const GemmArgs &a, hipStream_t s);
 int launch_qgemm_tile_fp8(const GemmArgs &a, hipStream_t s);
 int launch_group_sums(const void *x_bf16, int64_t rows, int K, float *sums, hipStream_t s);

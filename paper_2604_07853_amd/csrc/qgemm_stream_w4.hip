@@ -64,7 +64,16 @@ struct W4Params {
     int bpr, rpp;
     uint32_t bpr_magic;   // tid / bpr == (tid * bpr_magic) >> 20
     int map_mode;    // row maps copied to LDS up front: 0 no, 1 into the (still free) tile region, 2 into their own
+    // Routed mode (ids != null; offsets and the row maps are unused): problem row = pair id pr = t * topk + slot,
+    // expert ids[pr], activation row t or pr, output row pr.  Every workgroup finds its expert's pairs itself.
+    const int32_t *ids;
+    int n_ids;         // T * topk <= kIdsMax
+    int topk;
+    int x_per_token;   // activation row of pair pr: pr / topk if set, else pr
 };
+
+constexpr int kIdsMax = 4096;    // pairs a workgroup scans (8 per thread)
+constexpr int kIdsRows = 512;    // rows of one expert it can list: one per token, T <= 512
 
 // LDS bytes per activation row: the row plus 16 bytes, so consecutive rows skew by 4 banks.
 __host__ __device__ constexpr int x_stride(int K) { return K * 2 + 16; }
@@ -168,10 +177,62 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_kernel(W4Params p
 
     // ---- start-up: the whole row maps go to LDS while the expert offsets are on their way: 16-byte loads;
     // the last, partial quad of a map is fetched entry by entry
+    const bool routed = p.ids != nullptr;
     const bool map_in_lds = p.map_mode != 0;
-    // [M rounded up to 4] row_map, then the same for out_row_map
+    // [M rounded up to 4] row_map, then the same for out_row_map; routed mode: [kIdsRows] activation rows of
+    // this expert's pairs, [kIdsRows] pair ids, then the pair count of every wavefront's share of the ids
     int *tmp_map = (int *)(p.map_mode == 2 ? xs + kRows * stride : xs);
-    const int m4 = (p.M + 3) & ~3;
+    const int m4 = routed ? kIdsRows : (p.M + 3) & ~3;
+    int row0, Me;
+    if (routed) {
+        // Thread tid looks at pairs 8 tid .. 8 tid + 7.  Matches keep their order: the rows of an expert are its
+        // pairs by increasing pair id, the (token, slot) order a stable grouping gives.
+        const int base = tid * 8;
+        int idv[8];
+#pragma unroll
+        for (int q4 = 0; q4 < 2; ++q4) {
+            const int b4 = base + 4 * q4;
+            i32x4 v4 = {-1, -1, -1, -1};
+            if (b4 + 3 < p.n_ids) {
+                v4 = *(const i32x4 *)(p.ids + b4);
+            } else {
+                for (int k = 0; b4 + k < p.n_ids; ++k) v4[k] = p.ids[b4 + k];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) idv[4 * q4 + k] = v4[k];
+        }
+        uint32_t hits = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) hits |= (idv[k] == e) ? (1u << k) : 0u;
+        const int cnt = __popc(hits);
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        int *s_wcnt = tmp_map + 2 * kIdsRows;
+        if (lane == 63) s_wcnt[wave] = incl;
+        lds_barrier();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const int cw = s_wcnt[w];
+            before += w < wave ? cw : 0;
+            total += cw;
+        }
+        int rank = before + incl - cnt;
+        for (uint32_t hm = hits; hm; hm &= hm - 1) {
+            const int pr = base + __builtin_ctz(hm);
+            if (rank < kIdsRows) {
+                tmp_map[rank] = p.x_per_token ? pr / p.topk : pr;
+                tmp_map[m4 + rank] = pr;
+            }
+            ++rank;
+        }
+        row0 = 0;
+        Me = min(total, kIdsRows);
+    } else {
     if (map_in_lds) {
         constexpr int kPer = kMapMax / (4 * kThreads);
 #pragma unroll
@@ -193,15 +254,16 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_kernel(W4Params p
             }
         }
     }
-    const int row0 = p.offsets[e];
-    const int Me = p.offsets[e + 1] - row0;
+    row0 = p.offsets[e];
+    Me = p.offsets[e + 1] - row0;
+    }
     if (Me <= mh * kRows) return;
 
     bool first_pass = true;
     for (int m0 = mh * kRows; m0 < Me; m0 += kRows * m_split) {
         const int mrem = min(kRows, Me - m0);
         lds_barrier();  // the row map copy is complete / the previous pass is done with the LDS tile
-        const bool use_tmp = map_in_lds && first_pass;
+        const bool use_tmp = map_in_lds && (first_pass || routed);   // the routed list has its own LDS region
         if (tid < kRows) {
             // rows past the expert's end take the id of its last row (never loaded, results never stored)
             const int i = row0 + m0 + min(tid, mrem - 1);
@@ -375,7 +437,8 @@ template <int EPI, int MT, int R>
 int launch_cfg(const W4Params &p, hipStream_t s)
 {
     size_t lds = lds_bytes(p.K, MT);
-    if (p.map_mode == 2) lds += 8 * (size_t)((p.M + 3) & ~3);
+    if (p.ids) lds += 8 * (size_t)kIdsRows + 4 * kWaves;
+    else if (p.map_mode == 2) lds += 8 * (size_t)((p.M + 3) & ~3);
     if (lds > 160 * 1024) {
         set_error("qgemm (decode path): K=%d needs %zu bytes of LDS per workgroup, more than the 160 KiB of a CU", p.K, lds);
         return QARL_ERR_UNSUPPORTED;
@@ -421,6 +484,10 @@ int launch_one(const GemmArgs &a, hipStream_t s)
     p.K = a.K;
     p.out_f32 = a.out_f32;
     p.M = (int)a.M;
+    p.ids = a.ids;
+    p.n_ids = a.ids ? (int)a.M : 0;
+    p.topk = a.topk;
+    p.x_per_token = a.x_per_token;
     p.n_units = (EPI == QARL_EPI_SILU_MUL) ? (a.N / 2) / 16 : a.N / 32;
     // rows per expert the grid should cover in one pass: mean + 4 sigma of a uniform router
     const double mean = (double)a.M / (double)a.E;
@@ -454,6 +521,16 @@ int launch_one(const GemmArgs &a, hipStream_t s)
         set_error("qgemm (decode path): activations of one call must stay below 4 GiB");
         return QARL_ERR_UNSUPPORTED;
     }
+    if (a.ids) {
+        if (a.M > kIdsMax || a.topk <= 0 || a.M % a.topk != 0 || a.M / a.topk > kIdsRows || ((uintptr_t)a.ids & 15) != 0) {
+            set_error("qgemm (routed decode path): needs T <= %d, T * topk <= %d and 16-byte aligned ids", kIdsRows, kIdsMax);
+            return QARL_ERR_UNSUPPORTED;
+        }
+        p.row_map = p.out_row_map = p.offsets = nullptr;
+        p.map_mode = 2;
+        if (MT == 1) return launch_ring<EPI, 1>(p, s);
+        return launch_ring<EPI, 2>(p, s);
+    }
     // decode-sized batches: the row maps go to LDS while the expert offsets are still on their way
     p.map_mode = 0;
     if (a.M <= kMapMax && (a.row_map || a.out_row_map) && (((uintptr_t)a.row_map | (uintptr_t)a.out_row_map) & 15) == 0) {
@@ -473,6 +550,13 @@ bool qgemm_stream_w4_supported(int N, int K)
     // whole rows (K / 8 blocks of 16 bytes per row, at most one sweep of the workgroup)
     if (N % 32 != 0 || K % 256 != 0 || K > 2048) return false;
     return lds_bytes(K, 1) <= 160 * 1024;
+}
+
+bool qgemm_stream_w4_routed_supported(int N, int K, int T, int topk)
+{
+    if (!qgemm_stream_w4_supported(N, K) || T <= 0 || topk <= 0) return false;
+    if (T > kIdsRows || (int64_t)T * topk > kIdsMax) return false;
+    return lds_bytes(K, 1) + 8 * (size_t)kIdsRows + 4 * kWaves <= 160 * 1024;
 }
 
 int launch_qgemm_stream_w4(const GemmArgs &a, hipStream_t s)

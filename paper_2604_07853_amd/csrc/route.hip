@@ -307,6 +307,14 @@ __global__ __launch_bounds__(kSmallThreads) void group_small_kernel(const int32_
     }
 }
 
+int launch_route_only(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w, hipStream_t s)
+{
+    const int per_block = kRouteThreads / 64;
+    route_topk_kernel<<<dim3((T + per_block - 1) / per_block), dim3(kRouteThreads), 0, s>>>(
+        (const uint16_t *)logits, T, E, topk, renorm, ids, w, nullptr);
+    return check_hip(hipGetLastError(), "route_topk_kernel");
+}
+
 int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w,
                  int32_t *counts, int32_t *offsets, int32_t *pairs, int32_t *tokens, hipStream_t s)
 {

@@ -289,3 +289,74 @@ def test_decode_row_map_paths(q, oracle, E, N, K, T, topk):
                                sorted_pairs=d_pairs, T=T, topk=topk, path=q.QARL_PATH_DECODE)
     assert norm_err_bf16(out.float().cpu().numpy(), out_ref) <= TOL_BF16
     assert flip_fraction(np_bits(out), out_ref_bits) <= MAX_FLIPS
+
+
+@pytest.mark.parametrize("E,N,K,T,topk", [(8, 64, 2048, 500, 3),      # several row blocks per expert, partial last quad of ids
+                                          (4, 64, 512, 37, 3),        # 111 pairs
+                                          (6, 96, 768, 171, 5),       # 64-row blocks
+                                          (128, 64, 256, 512, 8)])    # the largest routed batch: 512 tokens, 4096 pairs
+def test_routed_mode_equals_grouped_decode(q, oracle, E, N, K, T, topk):
+    """qarl_qgemm_routed (every workgroup lists its expert's pairs from the router's ids) against the oracle and,
+    bit for bit, against the grouped decode path fed with the grouping of the same ids: plain epilogue with x per
+    token, SiLU*mul, and the combine on rows in pair order."""
+    seed = 1300 + K + T
+    w = synth.normal_bf16((E, N, K), 0.02, seed=seed)
+    x = synth.normal_bf16((T, K), 1.0, seed=seed + 1)
+    lg = synth.router_logits(T, E, seed + 2, zipf_s=1.1)
+    ids, wts = oracle.route(np_bits(lg), topk)
+    counts, offsets, pairs = oracle.group(ids, E)
+    M = T * topk
+    tok = (pairs // topk).astype(np.int32)
+    d_ids = _i32(np.asarray(ids).reshape(-1))
+    d_off, d_tok, d_pairs = _i32(offsets), _i32(tok), _i32(pairs)
+    d_w = torch.tensor(np.asarray(wts, dtype=np.float32), device="cuda")
+    codes, scales = oracle.quantize_int4(np_bits(w))
+    qw = q.qarl_quantize_weights(w.cuda())
+    inv = torch.tensor(pairs, dtype=torch.long, device="cuda")     # sorted position i holds pair pairs[i]
+    # plain epilogue, activation row = token: row pr of the routed result is row i of the grouped one, pairs[i] = pr
+    y_ref = oracle.qgemm_w4a16(np_bits(x), codes, scales, offsets, tok)
+    y_grp = q.qarl_qgemm_grouped(qw, x.cuda(), d_off, M, row_map=d_tok, out_dtype=q.QARL_OUT_F32,
+                                 path=q.QARL_PATH_DECODE)
+    y_rt = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    q.qarl_qgemm_routed(qw, x.cuda(), d_ids, T, topk, True, out=y_rt, out_dtype=q.QARL_OUT_F32)
+    assert norm_err(y_rt[inv].cpu().numpy(), y_ref) <= TOL_F32
+    assert torch.equal(y_rt[inv], y_grp)
+    # SiLU*mul
+    a_grp = q.qarl_qgemm_grouped(qw, x.cuda(), d_off, M, row_map=d_tok, epilogue=q.QARL_EPI_SILU_MUL,
+                                 path=q.QARL_PATH_DECODE)
+    a_rt = q.qarl_qgemm_routed(qw, x.cuda(), d_ids, T, topk, True, epilogue=q.QARL_EPI_SILU_MUL)
+    assert np.array_equal(np_bits(a_rt[inv]), np_bits(a_grp))
+    # combine: activation row = pair id
+    xp = x[torch.tensor(np.arange(M) // topk, dtype=torch.long)].contiguous()   # one row per pair, pair order
+    xg = xp[torch.tensor(pairs, dtype=torch.long)].contiguous()                 # the same rows in sorted order
+    out_grp = q.qarl_qgemm_grouped(qw, xg.cuda(), d_off, M, epilogue=q.QARL_EPI_COMBINE, combine_w=d_w,
+                                   sorted_pairs=d_pairs, T=T, topk=topk, path=q.QARL_PATH_DECODE)
+    out_rt = q.qarl_qgemm_routed(qw, xp.cuda(), d_ids, T, topk, False, epilogue=q.QARL_EPI_COMBINE, combine_w=d_w)
+    y2_ref = oracle.qgemm_w4a16(np_bits(xg), codes, scales, offsets)
+    out_ref, _ = oracle.combine(y2_ref, pairs, wts, T, topk)
+    assert norm_err_bf16(out_rt.float().cpu().numpy(), out_ref) <= TOL_BF16
+    assert np.array_equal(np_bits(out_rt), np_bits(out_grp))
+
+
+def test_routed_mode_errors_and_route_only(q):
+    w = synth.normal_bf16((64, 32, 256), 0.02, seed=3).cuda()
+    qw = q.qarl_quantize_weights(w)
+    x = synth.normal_bf16((600, 256), 1.0, seed=4).cuda()
+    ids = torch.zeros((600 * 8,), dtype=torch.int32, device="cuda")
+    with pytest.raises(q.QarlError) as ei:                       # more than 512 tokens
+        q.qarl_qgemm_routed(qw, x, ids, 600, 8, True)
+    assert ei.value.status == q.QARL_ERR_UNSUPPORTED
+    with pytest.raises(q.QarlError) as ei:                       # more than 4096 pairs
+        q.qarl_qgemm_routed(qw, x, ids, 500, 9, True)
+    assert ei.value.status == q.QARL_ERR_UNSUPPORTED
+    q8 = q.qarl_quantize_weights(w, q.QARL_FP8_E4M3_CH)
+    with pytest.raises(q.QarlError) as ei:                       # FP8 has no routed kernel
+        q.qarl_qgemm_routed(q8, x, ids, 16, 8, True)
+    assert ei.value.status == q.QARL_ERR_UNSUPPORTED
+    out = q.qarl_qgemm_routed(qw, x, ids, 0, 8, True)            # T = 0: nothing to do
+    assert out.shape[0] == 0
+    # the router without its grouping pass writes the same ids and weights
+    lg = synth.router_logits(300, 64, 9).cuda()
+    r1 = q.qarl_moe_route(lg, 4)
+    r2 = q.qarl_moe_route(lg, 4, group=False)
+    assert torch.equal(r1.ids, r2.ids) and torch.equal(r1.w, r2.w)
