@@ -27,7 +27,7 @@ MFMA_FP8_PEAK_TF = 5000.0
 # HBM bytes per gate_up launch of the headline step from two counter runs (2.000 x FETCH_SIZE + 1.000 x WRITE_SIZE,
 # the factors a plain copy kernel of known size gives): profiles/qgemm_stream_decode256_hbm_traffic.txt.
 # Counters cannot be read from inside this process, so the figure is stored; it belongs to the 256-token workload.
-GATE_UP_TRAFFIC_BYTES = 220441190
+GATE_UP_TRAFFIC_BYTES = 220271616
 
 
 def weight_bytes_w4a16(E, N, K):
