@@ -360,3 +360,21 @@ def test_routed_mode_errors_and_route_only(q):
     r1 = q.qarl_moe_route(lg, 4)
     r2 = q.qarl_moe_route(lg, 4, group=False)
     assert torch.equal(r1.ids, r2.ids) and torch.equal(r1.w, r2.w)
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_layer_is_reproducible_run_to_run(q, path):
+    """Wavefronts draw their weight tiles dynamically and workgroups finish in any order; no result may depend on
+    it: repeated runs of one layer give the same bits, interleaved with a different batch in between."""
+    E, H, I, T, topk = 64, 512, 256, 301, 4
+    gu, dn = synth.expert_weights(E, H, I, seed=77)
+    layer = q.MoELayer(q.qarl_quantize_weights(gu.cuda()), q.qarl_quantize_weights(dn.cuda()), T, topk, path)
+    x = synth.normal_bf16((T, H), 1.0, 78).cuda()
+    lg = synth.router_logits(T, E, 79, zipf_s=1.1).cuda()
+    x2 = synth.normal_bf16((T, H), 1.0, 80).cuda()
+    lg2 = synth.router_logits(T, E, 81).cuda()
+    first = layer.forward(x, lg).clone()
+    for _ in range(5):
+        layer.forward(x2, lg2)
+        again = layer.forward(x, lg)
+        assert torch.equal(first.view(torch.int16), again.view(torch.int16))
