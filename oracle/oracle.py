@@ -212,6 +212,27 @@ def mismatch(lp_learner, lp_sampler, seq_offsets, c=2.0):
     return delta, w, ws, wc
 
 
+def tbpo(lp_cur, lp_old, lp_smp, seq_offsets, adv, eps_low, eps_high, delta_low, delta_high, c=2.0):
+    """Sequence-level surrogate (section 3.2); returns dict(r, w_clip, r_clip, in_band, obj_seq, objective, grad)."""
+    a = _c(lp_cur, np.float64)
+    b = _c(lp_old, np.float64)
+    d = _c(lp_smp, np.float64)
+    so = _c(seq_offsets, np.int32)
+    av = _c(adv, np.float64)
+    S = so.size - 1
+    r = np.empty(S)
+    wc = np.empty(S)
+    rc = np.empty(S)
+    ib = np.empty(S, dtype=np.int32)
+    ob = np.empty(S)
+    J = np.zeros(1)
+    g = np.zeros(a.size)
+    lib().oracle_tbpo(_p(a), _p(b), _p(d), _p(so), C.c_int(S), _p(av), C.c_double(eps_low), C.c_double(eps_high),
+                      C.c_double(delta_low), C.c_double(delta_high), C.c_double(c), _p(r), _p(wc), _p(rc), _p(ib),
+                      _p(ob), _p(J), _p(g))
+    return dict(r=r, w_clip=wc, r_clip=rc, in_band=ib, obj_seq=ob, objective=float(J[0]), grad=g)
+
+
 def moe_ffn_w4a16(x_bits, logit_bits, gu_codes, gu_scales, dn_codes, dn_scales, topk=8, acc32=False):
     """Whole MoE layer (route -> gate_up -> SiLU*mul -> down -> combine), W4A16.
     Returns a dict with every intermediate."""

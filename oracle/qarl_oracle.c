@@ -5,9 +5,10 @@
  * weight quantization (integer and floating-point forms, paper section 2.2
  * "Quantization", the Quant/Dequant equations), the quantized GEMM of eq. (1)
  * and eq. (2), a softmax top-k router, the SiLU-gated expert FFN, the per-token
- * log-probability, and the token / sequence mismatch weights (eq. (3) and the
+ * log-probability, the token / sequence mismatch weights (eq. (3) and the
  * sequence-level definitions of section 3.2 and the appendix figure "Sequence
- * ratio and weight definition").
+ * ratio and weight definition"), and the sequence-level surrogate of section
+ * 3.2 ("Sequence Level Objectives") built from them.
  *
  * It shares no code, header, table or constant with the HIP library.  Only the
  * tests, the smoke check and the benchmark's cpu_baseline leg may call it; the
@@ -21,7 +22,8 @@
  *
  * Pins: tests/test_oracle_*.py (exact rational nearest-code checks, all 256
  * e4m3 patterns, full-sort routing, one-hot / exact-integer GEMM regimes,
- * closed-form log-probs).  Anything not covered there is "parity unpinned".
+ * closed-form log-probs, geometric-mean / finite-difference checks of the
+ * sequence objective).  Anything not covered there is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -389,4 +391,63 @@ void oracle_mismatch(const double *lp_learner, const double *lp_sampler,
         double cm = mean < -lc ? -lc : (mean > lc ? lc : mean);
         w_seq_clipped[s] = exp(cm);
     }
+}
+
+/* Sequence-level surrogate of section 3.2 ("Sequence Level Objectives"; ratio and weight as in
+ * the appendix figure "Sequence ratio and weight definition").  A response o of L tokens is one
+ * action whose probability is the geometric mean of its token probabilities, so in log space
+ *     r  = exp(mean_t (lp_current - lp_old)),      w = exp(mean_t (lp_old - lp_sampler)),
+ *     w~ = exp(clip(log w, -log c, log c))                    (the two-sided cap, c > 1),
+ *     r~ = clip(r, 1 - eps_low,   1 + eps_high)   if A >= 0   (the paper's bound [0, 1 + eps_h] is eps_low = 1),
+ *          clip(r, 1 - delta_low, 1 + delta_high) if A <  0,
+ *     objective of the response = w~ * r~ * A,
+ * and J is the mean over the responses that have tokens.  A response whose ratio leaves its band is
+ * masked out of the update: in_band = (lower <= r <= upper), decided on r and the bounds rounded to
+ * fp32 (the precision the GPU path compares in).  grad[t] = dJ/d lp_current[t] with w~ held constant
+ * (it does not depend on the current policy) = in_band * w~ * A * r / (L * S'), S' = responses with
+ * tokens.  An empty response has r = w = w~ = r~ = 1, objective 0, and does not count in S'. */
+void oracle_tbpo(const double *lp_cur, const double *lp_old, const double *lp_smp,
+                 const int32_t *seq_offsets, int S, const double *adv, double eps_low, double eps_high,
+                 double delta_low, double delta_high, double c, double *r_seq, double *w_clip,
+                 double *r_clip, int32_t *in_band, double *obj_seq, double *objective, double *grad)
+{
+    int nonempty = 0;
+    for (int s = 0; s < S; ++s)
+        if (seq_offsets[s + 1] > seq_offsets[s]) ++nonempty;
+    double total = 0.0;
+    for (int s = 0; s < S; ++s) {
+        const int lo = seq_offsets[s], hi = seq_offsets[s + 1];
+        const int L = hi - lo;
+        if (L <= 0) {
+            r_seq[s] = w_clip[s] = r_clip[s] = 1.0;
+            in_band[s] = 1;
+            obj_seq[s] = 0.0;
+            continue;
+        }
+        double sum_r = 0.0, sum_w = 0.0;
+        for (int t = lo; t < hi; ++t) {
+            sum_r += lp_cur[t] - lp_old[t];
+            sum_w += lp_old[t] - lp_smp[t];
+        }
+        const double r = exp(sum_r / L);
+        const double lc = log(c);
+        double lw = sum_w / L;
+        if (lw < -lc) lw = -lc;
+        if (lw > lc) lw = lc;
+        const double wt = exp(lw);
+        const double lower = adv[s] >= 0.0 ? 1.0 - eps_low : 1.0 - delta_low;
+        const double upper = adv[s] >= 0.0 ? 1.0 + eps_high : 1.0 + delta_high;
+        const float r32 = (float)r, lower32 = (float)lower, upper32 = (float)upper;
+        const int inside = (r32 >= lower32) && (r32 <= upper32);
+        const double rt = inside ? r : (r32 < lower32 ? lower : upper);
+        r_seq[s] = r;
+        w_clip[s] = wt;
+        r_clip[s] = rt;
+        in_band[s] = inside;
+        obj_seq[s] = wt * rt * adv[s];
+        total += obj_seq[s];
+        if (grad)
+            for (int t = lo; t < hi; ++t) grad[t] = inside ? wt * adv[s] * r / ((double)L * (double)nonempty) : 0.0;
+    }
+    *objective = nonempty ? total / (double)nonempty : 0.0;
 }
