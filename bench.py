@@ -251,6 +251,22 @@ def main():
         fl_lp = 2 * Tp * H * V
         extra["lm_head_logprob_16384x151936"] = {"ms": round(ms_lp, 3), "TFLOP/s": round(fl_lp / ms_lp / 1e9, 1),
                                                  "frac_mfma_bf16": round(fl_lp / ms_lp / 1e9 / MFMA_BF16_PEAK_TF, 4)}
+        # sequence-level surrogate (section 3.2) on the log-probs of that configuration: 8 responses x 2048 tokens.
+        # Two small launches over 0.26 MB: launch-bound, reported as time per call.
+        Sq, Lq = 8, Tp // 8
+        g = torch.Generator(device=dev)
+        g.manual_seed(60)
+        lp_o = -torch.rand((Tp,), generator=g, device=dev) * 5 - 0.01
+        lp_c = lp_o + torch.randn((Tp,), generator=g, device=dev) * 1e-3
+        lp_s = lp_o + torch.randn((Tp,), generator=g, device=dev) * 0.05
+        so = torch.arange(Sq + 1, dtype=torch.int32, device=dev) * Lq
+        adv = torch.randn((Sq,), generator=g, device=dev)
+        tb_out = q.qarl_tbpo_objective(lp_c, lp_o, lp_s, so, adv, 1.0, 0.0004, 0.0003, 0.0007, 2.0)
+        ms_tb = timed(lambda: q.qarl_tbpo_objective(lp_c, lp_o, lp_s, so, adv, 1.0, 0.0004, 0.0003, 0.0007, 2.0,
+                                                    out=tb_out), 50, 5)
+        tb_bytes = 4 * Tp * 4
+        extra["tbpo_objective_8x2048"] = {"ms": round(ms_tb, 4), "GB/s": round(tb_bytes / ms_tb / 1e6, 1),
+                                          "bytes": tb_bytes, "launches": 2}
         del wlm, ws, lp_layer, xp
 
         # FP8 W8A8 layer at 256 and 8192 tokens

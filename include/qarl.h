@@ -179,6 +179,32 @@ int qarl_logprob_mismatch(const float *lp_learner, const float *lp_sampler, int 
                           const int32_t *seq_offsets, int S, float tis_cap_c, float *delta,
                           float *token_w, float *seq_w, float *seq_w_clipped, void *stream);
 
+/* Sequence-level surrogate of section 3.2 ("Sequence Level Objectives"; ratio and weight as in the
+ * appendix figure "Sequence ratio and weight definition") on the log-probs the two calls above
+ * produce.  Response s = tokens [seq_offsets[s], seq_offsets[s+1]), L of them, is one action whose
+ * probability is the geometric mean of its token probabilities:
+ *   r_seq[s]         = exp(mean_t (lp_current[t] - lp_old[t]))
+ *   w_seq_clipped[s] = exp(clip(mean_t (lp_old[t] - lp_sampler[t]), -log c, log c)),  c = tis_cap_c > 1
+ *   r_clipped[s]     = clip(r_seq, 1 - eps_low,   1 + eps_high)    if advantage[s] >= 0
+ *                      clip(r_seq, 1 - delta_low, 1 + delta_high)  if advantage[s] <  0
+ *                      (the section's band [0, 1 + eps_h] for non-negative advantages is eps_low = 1)
+ *   in_band[s]       = 1 if the ratio lies inside its band (bounds included), else 0: a response
+ *                      outside is masked out of the update
+ *   objective_seq[s] = w_seq_clipped * r_clipped * advantage[s]
+ *   objective[0]     = mean of objective_seq over the responses that have tokens (0 if none)
+ *   grad_lp_current[t] = d objective / d lp_current[t], the mismatch weight held constant:
+ *                      in_band * w_seq_clipped * advantage * r_seq / (L * responses with tokens)
+ * A response without tokens has ratio and weights 1, objective 0 and does not count in the mean.
+ * All streams fp32 [T], advantage fp32 [S], seq_offsets int32 [S+1] ascending within [0, T].
+ * objective and objective_seq are required; r_seq, w_seq_clipped, r_clipped, in_band and
+ * grad_lp_current may each be NULL.  Tokens outside every response keep their old grad value.
+ * Sums run in a fixed order in fp64, exp in fp32.  Errors: INVALID_ARG. */
+int qarl_tbpo_objective(const float *lp_current, const float *lp_old, const float *lp_sampler, int T,
+                        const int32_t *seq_offsets, int S, const float *advantage, float eps_low,
+                        float eps_high, float delta_low, float delta_high, float tis_cap_c,
+                        float *r_seq, float *w_seq_clipped, float *r_clipped, int32_t *in_band,
+                        float *objective_seq, float *objective, float *grad_lp_current, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ QARL_OUT_BF16, QARL_OUT_F32 = 0, 1
 
 EXPORTS = ["qarl_last_error", "qarl_qgemm_workspace_bytes", "qarl_logprob_workspace_bytes",
            "qarl_quantize_weights", "qarl_quantize_rows_fp8", "qarl_moe_route", "qarl_qgemm_grouped",
-           "qarl_qgemm_routed", "qarl_token_logprob", "qarl_logprob_mismatch"]
+           "qarl_qgemm_routed", "qarl_token_logprob", "qarl_logprob_mismatch", "qarl_tbpo_objective"]
 
 
 class QarlError(RuntimeError):
@@ -65,6 +65,8 @@ def lib():
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.qarl_logprob_mismatch.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_float,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.qarl_tbpo_objective.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
+                                          C.c_float, C.c_float, C.c_float, C.c_float, C.c_float] + [C.c_void_p] * 8
         for name in EXPORTS[3:]:
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -291,3 +293,32 @@ class MoELayer:
                                sorted_pairs=r.pairs, T=self.T, topk=self.topk, out=self.out, path=self.path,
                                ws=self.ws)
         return self.out
+
+
+def qarl_tbpo_objective(lp_current, lp_old, lp_sampler, seq_offsets, advantage, eps_low, eps_high, delta_low,
+                        delta_high, tis_cap_c=2.0, want_grad=True, out=None):
+    """Sequence-level surrogate of section 3.2; see include/qarl.h.
+    Returns dict(r, w_clip, r_clip, in_band, obj_seq, objective[, grad]); `out` = a dict from an earlier call of
+    the same sizes, whose buffers are written again."""
+    T = lp_current.numel()
+    S = seq_offsets.numel() - 1
+    dev = lp_current.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    if out is not None:
+        r, wc, rc, ib, ob, J = out["r"], out["w_clip"], out["r_clip"], out["in_band"], out["obj_seq"], out["objective"]
+        g = out.get("grad") if want_grad else None
+    else:
+        r = torch.empty((S,), **f32)
+        wc = torch.empty((S,), **f32)
+        rc = torch.empty((S,), **f32)
+        ib = torch.empty((S,), dtype=torch.int32, device=dev)
+        ob = torch.empty((S,), **f32)
+        J = torch.empty((1,), **f32)
+        g = torch.zeros((T,), **f32) if want_grad else None
+    _check(lib().qarl_tbpo_objective(_ptr(lp_current), _ptr(lp_old), _ptr(lp_sampler), T, _ptr(seq_offsets), S,
+                                     _ptr(advantage), eps_low, eps_high, delta_low, delta_high, tis_cap_c, _ptr(r),
+                                     _ptr(wc), _ptr(rc), _ptr(ib), _ptr(ob), _ptr(J), _ptr(g), _stream()))
+    out = dict(r=r, w_clip=wc, r_clip=rc, in_band=ib, obj_seq=ob, objective=J)
+    if want_grad:
+        out["grad"] = g
+    return out

@@ -6,7 +6,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqarl.so")
-SOURCES = ["api.hip", "quantize.hip", "route.hip", "qgemm_stream_fp8.hip", "qgemm_stream_w4.hip", "qgemm_tile.hip", "qgemm_tile_fp8.hip", "combine.hip", "logprob.hip"]
+SOURCES = ["api.hip", "quantize.hip", "route.hip", "qgemm_stream_fp8.hip", "qgemm_stream_w4.hip", "qgemm_tile.hip", "qgemm_tile_fp8.hip", "combine.hip", "logprob.hip", "tbpo.hip"]
 
 
 def hipcc():

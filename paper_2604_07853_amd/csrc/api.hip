@@ -352,6 +352,40 @@ int qarl_qgemm_routed(const qarl_qweight *W, const void *x, int x_per_token, con
     return QARL_OK;
 }
 
+int qarl_tbpo_objective(const float *lp_current, const float *lp_old, const float *lp_sampler, int T,
+                        const int32_t *seq_offsets, int S, const float *advantage, float eps_low, float eps_high,
+                        float delta_low, float delta_high, float tis_cap_c, float *r_seq, float *w_seq_clipped,
+                        float *r_clipped, int32_t *in_band, float *objective_seq, float *objective,
+                        float *grad_lp_current, void *stream)
+{
+    if (T < 0 || S < 0) {
+        set_error("qarl_tbpo_objective: negative T or S");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!(tis_cap_c > 1.0f) || !std::isfinite(tis_cap_c)) {
+        set_error("qarl_tbpo_objective: cap c must exceed 1 (got %g)", (double)tis_cap_c);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!(eps_low >= 0.f) || !(eps_high >= 0.f) || !(delta_low >= 0.f) || !(delta_high >= 0.f)) {
+        set_error("qarl_tbpo_objective: band widths must be non-negative");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!objective || (S > 0 && !objective_seq)) {
+        set_error("qarl_tbpo_objective: objective and objective_seq are required");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (S > 0 && (!seq_offsets || !advantage || (T > 0 && (!lp_current || !lp_old || !lp_sampler)))) {
+        set_error("qarl_tbpo_objective: null pointer");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (S == 0) {   // no response: J = 0, written by a one-element fill
+        return launch_fill_f32(objective, 1, 0.f, (hipStream_t)stream);
+    }
+    return launch_tbpo(lp_current, lp_old, lp_sampler, seq_offsets, S, advantage, eps_low, eps_high, delta_low,
+                       delta_high, tis_cap_c, r_seq, w_seq_clipped, r_clipped, in_band, objective_seq, objective,
+                       grad_lp_current, (hipStream_t)stream);
+}
+
 int qarl_logprob_mismatch(const float *lp_learner, const float *lp_sampler, int T, const int32_t *seq_offsets, int S,
                           float tis_cap_c, float *delta, float *token_w, float *seq_w, float *seq_w_clipped,
                           void *stream)

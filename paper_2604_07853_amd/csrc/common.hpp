@@ -157,6 +157,11 @@ int launch_combine(const float *y_pair_order, const float *w, int T, int topk, i
 int launch_logprob(const void *h, const void *wlm, const int32_t *target, int T, int H, int V,
                    float inv_temp, float *logprob, void *ws, hipStream_t s);
 size_t logprob_ws_bytes(int T, int H, int V);
+int launch_fill_f32(float *p, int n, float v, hipStream_t s);
+int launch_tbpo(const float *lp_cur, const float *lp_old, const float *lp_smp, const int32_t *seq_offsets, int S,
+                const float *adv, float eps_low, float eps_high, float delta_low, float delta_high, float c,
+                float *r_seq, float *w_clip, float *r_clip, int32_t *in_band, float *obj_seq, float *objective,
+                float *grad, hipStream_t s);
 int launch_mismatch(const float *lp_a, const float *lp_b, int T, const int32_t *seq_offsets, int S, float c,
                     float *delta, float *token_w, float *seq_w, float *seq_wc, hipStream_t s);
 
