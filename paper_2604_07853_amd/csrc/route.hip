@@ -152,19 +152,23 @@ __global__ __launch_bounds__(kCountThreads) void count_experts_kernel(const int3
     if (threadIdx.x < E && s_hist[threadIdx.x] != 0) atomicAdd(&counts[threadIdx.x], s_hist[threadIdx.x]);
 }
 
-// One workgroup per expert: its offset is the sum of the counts before it; it then walks all
-// pairs in ascending order and compacts the ones routed to it, which keeps (t, slot) order.
+// One workgroup per expert: its offset is the sum of the counts before it; it then compacts the pairs routed
+// to it in ascending pair order, which keeps (t, slot) order.  Every wavefront owns one contiguous range of the
+// pairs and walks it 256 pairs at a time (4 consecutive pairs per lane, coalesced), once to count its hits and,
+// after the only barrier (an exclusive scan of the 16 wavefront totals), once more to place them: inside the
+// loop a wavefront-level prefix sum is all that is needed.  The ids are read twice; the second read hits cache.
 constexpr int kGroupThreads = 1024;
-constexpr int kPairsPerThread = 4;
+constexpr int kGroupWaves = kGroupThreads / 64;
+constexpr int kGroupStep = 256;   // pairs per wavefront and step
 
 __global__ __launch_bounds__(kGroupThreads) void group_by_expert_kernel(const int32_t *__restrict__ ids,
                                                                        int n_pairs, int E, int topk,
                                                                        const int32_t *__restrict__ counts,
                                                                        int32_t *__restrict__ offsets,
                                                                        int32_t *__restrict__ pairs,
-                                                                       int32_t *__restrict__ tokens)
+                                                                       int32_t *__restrict__ tokens, int ids_aligned)
 {
-    __shared__ int s_wave[kGroupThreads / 64];
+    __shared__ int s_wave[kGroupWaves];
     __shared__ int s_base;
     const int e = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -177,49 +181,54 @@ __global__ __launch_bounds__(kGroupThreads) void group_by_expert_kernel(const in
     __syncthreads();
     if (threadIdx.x == 0) {
         int b = 0;
-        for (int i = 0; i < kGroupThreads / 64; ++i) b += s_wave[i];
+        for (int i = 0; i < kGroupWaves; ++i) b += s_wave[i];
         s_base = b;
         offsets[e] = b;
         if (e == E - 1) offsets[E] = b + counts[e];
     }
+    // this wavefront's range of pairs: a multiple of the step, so every 16-byte load is aligned
+    const int steps = (n_pairs + kGroupWaves * kGroupStep - 1) / (kGroupWaves * kGroupStep);
+    const int lo = wave * steps * kGroupStep;
+    const int hi = min(n_pairs, lo + steps * kGroupStep);
+    auto hits_of = [&](int p) -> uint32_t {   // bit j set: pair p + j goes to this expert
+        uint32_t h = 0;
+        if (ids_aligned && p + 3 < n_pairs) {
+            const i32x4 v = *(const i32x4 *)(ids + p);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) h |= (v[j] == e) ? (1u << j) : 0u;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) h |= (p + j < n_pairs && ids[p + j] == e) ? (1u << j) : 0u;
+        }
+        return h;
+    };
+    int cnt = 0;
+    for (int p0 = lo; p0 < hi; p0 += kGroupStep) cnt += __popc(hits_of(p0 + lane * 4));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+    __syncthreads();   // s_base is written, the offset pass is done with s_wave
+    if (lane == 0) s_wave[wave] = cnt;
     __syncthreads();
     int running = s_base;
-    const int chunk = kGroupThreads * kPairsPerThread;
-    for (int p0 = 0; p0 < n_pairs; p0 += chunk) {
-        const int p = p0 + threadIdx.x * kPairsPerThread;
-        int hit[kPairsPerThread];
-        int cnt = 0;
-#pragma unroll
-        for (int j = 0; j < kPairsPerThread; ++j) {
-            hit[j] = (p + j < n_pairs) && (ids[p + j] == e);
-            cnt += hit[j];
-        }
-        // exclusive scan of cnt over the workgroup
-        int incl = cnt;
+    for (int i = 0; i < wave; ++i) running += s_wave[i];
+    for (int p0 = lo; p0 < hi; p0 += kGroupStep) {
+        const int p = p0 + lane * 4;
+        uint32_t h = hits_of(p);
+        const int c = __popc(h);
+        int incl = c;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
-            int v = __shfl_up(incl, o, 64);
+            const int v = __shfl_up(incl, o, 64);
             if (lane >= o) incl += v;
         }
-        __syncthreads();  // previous iteration's readers of s_wave are done
-        if (lane == 63) s_wave[wave] = incl;
-        __syncthreads();
-        int before = 0, total = 0;
-#pragma unroll
-        for (int i = 0; i < kGroupThreads / 64; ++i) {
-            int v = s_wave[i];
-            if (i < wave) before += v;
-            total += v;
+        int pos = running + incl - c;
+        for (; h; h &= h - 1) {
+            const int pj = p + __builtin_ctz(h);
+            pairs[pos] = pj;
+            tokens[pos] = pj / topk;
+            ++pos;
         }
-        int pos = running + before + incl - cnt;
-#pragma unroll
-        for (int j = 0; j < kPairsPerThread; ++j)
-            if (hit[j]) {
-                pairs[pos] = p + j;
-                tokens[pos] = (p + j) / topk;
-                ++pos;
-            }
-        running += total;
+        running += __shfl(incl, 63, 64);
     }
 }
 
@@ -341,7 +350,7 @@ int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t
         if (rc) return rc;
     }
     group_by_expert_kernel<<<dim3(E), dim3(kGroupThreads), 0, s>>>(ids, T * topk, E, topk, counts, offsets,
-                                                                   pairs, tokens);
+                                                                   pairs, tokens, ((uintptr_t)ids & 15) == 0);
     return check_hip(hipGetLastError(), "group_by_expert_kernel");
 }
 

@@ -129,6 +129,28 @@ def test_route_exact(q, oracle, T, E, topk, zipf):
     assert np.allclose(gw.sum(axis=1), 1.0, atol=1e-6)
 
 
+@pytest.mark.parametrize("T,E,topk", [(701, 64, 3), (5000, 128, 8), (4099, 256, 5)])
+def test_grouping_large_batches_any_alignment(q, oracle, T, E, topk):
+    """The large-batch grouping (one workgroup per expert, a contiguous range of pairs per wavefront): pair counts
+    that leave ragged tails in the last wavefront's range and in the last 4-pair load, experts without tokens
+    (Zipf), and an ids buffer that is not 16-byte aligned (the scalar-load path)."""
+    lg = synth.router_logits(T, E, seed=3 * T + E, zipf_s=1.3)
+    ids, w = oracle.route(np_bits(lg), topk)
+    counts, offsets, pairs = oracle.group(ids, E)
+    for shift in (0, 1):
+        r = q.Routing(T, E, topk, "cuda")
+        store = torch.empty((T * topk + 4,), dtype=torch.int32, device="cuda")
+        r.ids = store[shift:shift + T * topk].view(T, topk)           # shift = 1: 4 bytes off a 16-byte boundary
+        assert (r.ids.data_ptr() % 16 == 0) == (shift == 0)
+        q.qarl_moe_route(lg.cuda(), topk, out=r)
+        torch.cuda.synchronize()
+        assert np.array_equal(r.ids.cpu().numpy(), ids)
+        assert np.array_equal(r.counts.cpu().numpy(), counts)
+        assert np.array_equal(r.offsets.cpu().numpy(), offsets)
+        assert np.array_equal(r.pairs.cpu().numpy(), pairs)
+        assert np.array_equal(r.tokens.cpu().numpy(), pairs // topk)
+
+
 def test_route_empty_and_errors(q):
     lg = torch.empty((0, 128), dtype=torch.bfloat16, device="cuda")
     r = q.qarl_moe_route(lg, 8)
