@@ -1,12 +1,14 @@
-// Grouped quantized GEMM, MFMA-tiled ("prefill" / training-forward) path: the same
-// contraction as the weight-streaming path (eq. (1) / eq. (2) of section 2.2), on the same
-// codes and scales and with the same exact dequantized weight s*q, for experts that see
-// hundreds to thousands of token rows, where the path is a dense contraction.
+// Grouped quantized GEMM, MFMA-tiled ("prefill" / training-forward) path for W4A16: the same
+// contraction as the weight-streaming path (eq. (1) of section 2.2), on the same codes and
+// scales and with the same exact dequantized weight s*q, for experts that see hundreds to
+// thousands of token rows, where the path is a dense contraction.  (FP8: qgemm_tile_fp8.hip.)
 //
 // A workgroup owns a (32*MS)-token x 256-column tile of one expert.  Its eight wavefronts split
 // the columns: each owns 32 of them as MS v_mfma_f32_32x32x16 tiles, so no packed weight is read
 // or expanded twice in a workgroup.  Token rows are gathered once per workgroup into a
-// double-buffered LDS tile (one 128-k scale group per step); packed weights go global ->
+// double-buffered LDS tile (one 128-k scale group per step) by asynchronous global -> LDS copies,
+// 16-byte chunks XOR-swizzled with the row so that copies and operand reads are free of bank
+// conflicts; packed weights go global ->
 // registers and are expanded there, so the LDS only carries the activation operand.  Small
 // wavefront tiles keep the register count at 128, four wavefronts per SIMD from two workgroups
 // that run out of step: global-load latency and the VALU work of the expansion are hidden by the
@@ -26,14 +28,12 @@ namespace qarl {
 constexpr int kBN = 256;
 constexpr int kTileWaves = kBN / 32;          // each wavefront owns 32 columns
 constexpr int kTileThreads = 64 * kTileWaves;
-constexpr int kAStrideB16 = kGroup * 2 + 16;  // bytes per LDS row, bf16 activations
-constexpr int kAStrideF8 = kGroup + 16;       // bytes per LDS row, e4m3 activations
+constexpr int kARowB = kGroup * 2;            // bytes per LDS row: 128 bf16, no padding (chunks are swizzled)
 
 struct TileParams {
     const uint32_t *codes;
     const void *scales;
     const void *x;
-    const float *x_scales;
     const float *x_group_sums;
     const int32_t *row_map;
     const int32_t *out_row_map;
@@ -46,19 +46,17 @@ struct TileParams {
 };
 
 // MS: 32-row token tiles per wavefront (workgroup tile = 32 MS tokens x 256 columns).
-template <int FMT, int EPI, int MS>
+template <int EPI, int MS>
 __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kernel(TileParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
     constexpr bool kSilu = (EPI == QARL_EPI_SILU_MUL);
     constexpr int kBM = 32 * MS;
     constexpr int kThreads = kTileThreads;
-    constexpr int kStride = kInt4 ? kAStrideB16 : kAStrideF8;
+    constexpr int kStride = kARowB;
     constexpr int kBufBytes = kBM * kStride + kBM * 4;  // tile + per-row group sums
     __shared__ __attribute__((aligned(16))) int s_rows[kBM];   // activation row of each tile row (clamped to a valid one)
     __shared__ __attribute__((aligned(16))) int s_orow[kBM];   // output row, -1 past the expert's last row
-    __shared__ __attribute__((aligned(16))) float s_xs[kBM];   // fp8: activation scale of the row
 
     const int tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
@@ -111,7 +109,6 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
         const int xrow = p.row_map ? p.row_map[i] : i;
         s_rows[tid] = xrow;
         s_orow[tid] = tid < mrem ? (p.out_row_map ? p.out_row_map[i] : i) : -1;
-        if (!kInt4) s_xs[tid] = p.x_scales[xrow];
     }
     lds_barrier();
 
@@ -131,55 +128,45 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
     // columns past N read row 0 of the expert (valid data, results never stored)
     const int64_t wr = (int64_t)e * N + (tile_ok ? nrow : 0);
     // Byte offsets from the (uniform) array bases; the launcher checks that every array is below 4 GiB.
-    //   int4 codes: block (16-row tile, group g) is 1 KiB; this lane's row is wr % 16 of tile wr / 16 and it
-    //   takes the 16-byte pieces q = 2h + u (k in [32 q, +32)).  fp8 codes: row-major bytes, k in [64 h, +64).
-    uint32_t woff = kInt4 ? (uint32_t)((wr / 16) * G * 1024 + (wr % 16) * 16 + h * 512)
-                          : (uint32_t)(wr * K + h * 64);
-    uint32_t soff = (uint32_t)(wr * G * 2);   // int4: the row's bf16 scales
+    //   codes: block (16-row tile, group g) is 1 KiB; this lane's row is wr % 16 of tile wr / 16 and it
+    //   takes the 16-byte pieces q = 2h + u (k in [32 q, +32)).
+    const uint32_t woff = (uint32_t)((wr / 16) * G * 1024 + (wr % 16) * 16 + h * 512);
+    const uint32_t soff = (uint32_t)(wr * G * 2);   // the row's bf16 scales
 
-    // ---- activation tile: kBM rows x 128 k, 16-byte blocks; consecutive lanes cover one row
-    constexpr int kBlkPerRow = kInt4 ? 16 : 8;
-    static_assert((kBM * kBlkPerRow) % kThreads == 0, "tile / thread mismatch");
-    constexpr int kARegs = (kBM * kBlkPerRow) / kThreads;
-    u32x4 ar[kARegs];
-    float gsum = 0.f;  // W4A16: -1.5 * sum of this thread's row over the group (threads < kBM)
+    // ---- activation tile: kBM rows x 128 k by asynchronous copies.  A wavefront instruction moves 4 rows x 256
+    // bytes (lane L: row L / 16, LDS chunk L % 16); chunk q of row r sits at r * 256 + (q ^ (r & 15)) * 16, so
+    // the lane fetches the chunk that belongs there.
+    constexpr int kARegs = (kBM * 16) / kThreads;
     const unsigned char *arow[kARegs];
 #pragma unroll
     for (int u = 0; u < kARegs; ++u) {
-        const int idx = u * kThreads + tid;
-        const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
-        arow[u] = (const unsigned char *)p.x + (int64_t)s_rows[r] * K * (kInt4 ? 2 : 1) + b * 16;
+        const int r = u * (kThreads / 16) + (tid >> 4);
+        const int q = (lane & 15) ^ (r & 15);
+        arow[u] = (const unsigned char *)p.x + (int64_t)s_rows[r] * K * 2 + q * 16;
     }
     const float *gsrow = p.x_group_sums + (int64_t)s_rows[tid % kBM] * G;
-    auto load_a = [&](int g) {
-        if (kInt4 && tid < kBM) gsum = gsrow[g];
-#pragma unroll
-        for (int u = 0; u < kARegs; ++u) ar[u] = *(const u32x4 *)(arow[u] + g * kGroup * (kInt4 ? 2 : 1));
-    };
-    auto store_a = [&](int buf) {
+    auto copy_a = [&](int g, int buf) {
         unsigned char *xs = smem + buf * kBufBytes;
-        float *sx = (float *)(xs + kBM * kStride);
-        if (kInt4 && tid < kBM) sx[tid] = gsum;
 #pragma unroll
-        for (int u = 0; u < kARegs; ++u) {
-            const int idx = u * kThreads + tid;
-            const int r = idx / kBlkPerRow, b = idx % kBlkPerRow;
-            *(u32x4 *)(xs + r * kStride + b * 16) = ar[u];
-        }
+        for (int u = 0; u < kARegs; ++u)
+            copy16_to_lds(arow[u] + g * kGroup * 2, xs + (u * (kThreads / 16) + wn * 4) * kStride);
+        if (tid < kBM)   // whole wavefronts: kBM is a multiple of 64
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gsrow + g),
+                                             (__attribute__((address_space(3))) void *)(xs + kBM * kStride + (tid & ~63) * 4), 4, 0, 0);
     };
 
     // ---- packed weights of one group
-    constexpr int kWRegs = kInt4 ? 2 : 4;  // 16-byte loads per lane
+    constexpr int kWRegs = 2;  // 16-byte loads per lane
     struct BRegs {
         u32x4 w[kWRegs];
         uint32_t s;
     };
     auto load_b = [&](BRegs &dst, int g) {
         const unsigned char *wb = (const unsigned char *)p.codes;
-        const uint32_t o = woff + (uint32_t)g * (kInt4 ? 1024u : 128u);
+        const uint32_t o = woff + (uint32_t)g * 1024u;
 #pragma unroll
-        for (int u = 0; u < kWRegs; ++u) dst.w[u] = *(const u32x4 *)(wb + (o + (kInt4 ? u * 256u : u * 16u)));
-        dst.s = kInt4 ? *(const uint16_t *)((const unsigned char *)p.scales + (soff + (uint32_t)g * 2u)) : 0;
+        for (int u = 0; u < kWRegs; ++u) dst.w[u] = *(const u32x4 *)(wb + (o + u * 256u));
+        dst.s = *(const uint16_t *)((const unsigned char *)p.scales + (soff + (uint32_t)g * 2u));
     };
 
     f32x16 acc[MS];
@@ -189,82 +176,67 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
         for (int i = 0; i < 16; ++i) acc[ms][i] = 0.f;
 
     // One 128-k step on the LDS buffer `buf` with the weights in `b`.
-    const int afrag = c * kStride + h * (kInt4 ? 128 : 64);   // this lane's operand read: rows c (+32 ms), its half of the k range
+    const int afrag = c * kStride;   // this lane's operand read: row c (+32 ms); chunk 8 h + j, swizzled
     auto step = [&](const BRegs &b, int buf) {
         const unsigned char *xs = smem + buf * kBufBytes + afrag;
         const float *sx = (const float *)(smem + buf * kBufBytes + kBM * kStride);
-        if (kInt4) {
-            f32x16 ag[MS];
+        f32x16 ag[MS];
 #pragma unroll
-            for (int ms = 0; ms < MS; ++ms)
+        for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    const f32x4 init = *(const f32x4 *)(sx + ms * 32 + 8 * i4 + 4 * h);
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const f32x4 init = *(const f32x4 *)(sx + ms * 32 + 8 * i4 + 4 * h);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) ag[ms][i4 * 4 + i] = init[i];
-                }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bf16x8 bw = unpack_int4_word(b.w[j >> 2][j & 3]);
-#pragma unroll
-                for (int ms = 0; ms < MS; ++ms) {
-                    const bf16x8 a = *(const bf16x8 *)(xs + ms * 32 * kStride + j * 16);
-                    ag[ms] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bw, ag[ms], 0, 0, 0);
-                }
+                for (int i = 0; i < 4; ++i) ag[ms][i4 * 4 + i] = init[i];
             }
-            const float s16 = 16.f * bf16_bits_to_f32(b.s);
 #pragma unroll
-            for (int ms = 0; ms < MS; ++ms)
+        for (int j = 0; j < 8; ++j) {
+            const bf16x8 bw = unpack_int4_word(b.w[j >> 2][j & 3]);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[ms][i] = fmaf(s16, ag[ms][i], acc[ms][i]);
-        } else {
-            // lane (c,h): slice j covers the 8 bytes k in [64 h + 8 j, +8); one 16-byte read feeds two slices
-#pragma unroll
-            for (int jp = 0; jp < 4; ++jp) {
-                const u32x4 w = b.w[jp];
-#pragma unroll
-                for (int ms = 0; ms < MS; ++ms) {
-                    const u32x4 a = *(const u32x4 *)(xs + ms * 32 * kStride + jp * 16);
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const long av = (long)(((uint64_t)a[2 * t + 1] << 32) | a[2 * t]);
-                        const long bv = (long)(((uint64_t)w[2 * t + 1] << 32) | w[2 * t]);
-                        acc[ms] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(av, bv, acc[ms], 0, 0, 0);
-                    }
-                }
+            for (int ms = 0; ms < MS; ++ms) {
+                const bf16x8 a = *(const bf16x8 *)(xs + ms * 32 * kStride + (((8 * h + j) ^ (c & 15)) << 4));
+                ag[ms] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bw, ag[ms], 0, 0, 0);
             }
         }
+        const float s16 = 16.f * bf16_bits_to_f32(b.s);
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ms][i] = fmaf(s16, ag[ms][i], acc[ms][i]);
     };
 
-    // Two steps per trip so that the two weight register sets swap roles without copies.
+    // Two steps per trip so that the two weight register sets swap roles without copies.  The weight registers
+    // of a step are touched before the next copies and loads go out: the compiler waits for every outstanding
+    // vector load at the first use of a loaded register while asynchronous copies are in flight, and at that
+    // point nothing is.
     BRegs b0, b1;
-    load_a(0);
+    b0.s = 0;
+    b1.s = 0;
+    copy_a(0, 0);
     load_b(b0, 0);
-    store_a(0);
-    lds_barrier();
+    copy_barrier();
     for (int g = 0; g < G; g += 2) {
+        asm volatile("" : "+v"(b0.w[0]), "+v"(b0.w[1]), "+v"(b0.s));
         if (g + 1 < G) {
-            load_a(g + 1);
+            copy_a(g + 1, 1);
             load_b(b1, g + 1);
         }
         step(b0, 0);
-        if (g + 1 < G) store_a(1);
-        lds_barrier();
+        copy_barrier();
         if (g + 1 >= G) break;
+        asm volatile("" : "+v"(b1.w[0]), "+v"(b1.w[1]), "+v"(b1.s));
         if (g + 2 < G) {
-            load_a(g + 2);
+            copy_a(g + 2, 0);
             load_b(b0, g + 2);
         }
         step(b1, 1);
-        if (g + 2 < G) store_a(0);
-        lds_barrier();
+        copy_barrier();
     }
 
     // ---- epilogue: lane (c,h), register i -> token row 8*(i/4) + 4h + i%4, column c of the tile.
     // A lane holds one column of 16 rows, so a direct store would move 4 (or 2) bytes per lane.  The results
     // take a turn through the activation buffers, which are free after the loop's last barrier, and leave as
     // 16-byte pieces of whole 128-byte row segments.
-    const float swn = kInt4 ? 1.f : ((const float *)p.scales)[wr];
     static_assert(2 * kBufBytes >= kBM * (kBN / 2) * 2 && 2 * kBufBytes >= (kThreads / 64) * 32 * 32 * 4, "epilogue tile does not fit");
     if (kSilu) {
         // workgroup tile [kBM rows][128 columns] bf16 in LDS
@@ -276,11 +248,6 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
                 f32x4 vv;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) vv[i] = acc[ms][i4 * 4 + i];
-                if (!kInt4) {
-                    const f32x4 xs4 = *(const f32x4 *)(s_xs + ms * 32 + 8 * i4 + 4 * h);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) vv[i] *= xs4[i] * swn;
-                }
                 // Registers i and i+1 trade 16-lane rows: afterwards every lane holds a gate value
                 // and the up value of the same column; lanes c < 16 for row i, lanes c >= 16 for row i+1.
 #pragma unroll
@@ -320,11 +287,6 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
                 f32x4 vv;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) vv[i] = acc[ms][i4 * 4 + i];
-                if (!kInt4) {
-                    const f32x4 xs4 = *(const f32x4 *)(s_xs + ms * 32 + 8 * i4 + 4 * h);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) vv[i] *= xs4[i] * swn;
-                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) ot[(8 * i4 + 4 * h + i) * 32 + c] = vv[i];
             }
@@ -351,10 +313,9 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
     }
 }
 
-template <int FMT, int EPI, int MS>
+template <int EPI, int MS>
 static int launch_cfg(const GemmArgs &a, hipStream_t s)
 {
-    constexpr bool kInt4 = (FMT == QARL_W4A16_G128);
     constexpr int kBM = 32 * MS;
     if (a.E > 256) {
         set_error("qgemm (prefill path): at most 256 experts (got %d)", a.E);
@@ -365,7 +326,7 @@ static int launch_cfg(const GemmArgs &a, hipStream_t s)
         return QARL_ERR_UNSUPPORTED;
     }
     const int64_t n_w = (int64_t)a.E * a.N * a.K;
-    if ((kInt4 ? n_w / 2 : n_w) >= (1LL << 32)) {
+    if (n_w / 2 >= (1LL << 32)) {
         set_error("qgemm (prefill path): quantized weights of one call must stay below 4 GiB");
         return QARL_ERR_UNSUPPORTED;
     }
@@ -373,7 +334,6 @@ static int launch_cfg(const GemmArgs &a, hipStream_t s)
     p.codes = (const uint32_t *)a.codes;
     p.scales = a.scales;
     p.x = a.x;
-    p.x_scales = a.x_scales;
     p.x_group_sums = a.x_group_sums;
     p.row_map = a.row_map;
     p.out_row_map = a.out_row_map;
@@ -392,9 +352,9 @@ static int launch_cfg(const GemmArgs &a, hipStream_t s)
     }
     p.m_slots = (int)slots;
     p.total = (int)total;
-    const size_t lds = 2 * ((size_t)kBM * (kInt4 ? kAStrideB16 : kAStrideF8) + kBM * 4);
+    const size_t lds = 2 * ((size_t)kBM * kARowB + kBM * 4);
     static bool attr_done = false;
-    auto kern = qgemm_tile_kernel<FMT, EPI, MS>;
+    auto kern = qgemm_tile_kernel<EPI, MS>;
     if (!attr_done) {
         int rc = check_hip(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
                            "hipFuncSetAttribute(tile)");
@@ -405,10 +365,10 @@ static int launch_cfg(const GemmArgs &a, hipStream_t s)
     return check_hip(hipGetLastError(), "qgemm_tile_kernel");
 }
 
-template <int FMT, int EPI>
+template <int EPI>
 static int launch_one(const GemmArgs &a, hipStream_t s)
 {
-    return launch_cfg<FMT, EPI, 2>(a, s);
+    return launch_cfg<EPI, 2>(a, s);
 }
 
 // sums[row][g] = -1.5 * sum over the 128 k of group g of x[row][k]: the start value of a group's
@@ -443,8 +403,7 @@ int launch_group_sums(const void *x_bf16, int64_t rows, int K, float *sums, hipS
 int launch_qgemm_tile(const GemmArgs &a, hipStream_t s)
 {
     if (a.fmt == QARL_W4A16_G128)
-        return a.epilogue == QARL_EPI_SILU_MUL ? launch_one<QARL_W4A16_G128, QARL_EPI_SILU_MUL>(a, s)
-                                               : launch_one<QARL_W4A16_G128, QARL_EPI_NONE>(a, s);
+        return a.epilogue == QARL_EPI_SILU_MUL ? launch_one<QARL_EPI_SILU_MUL>(a, s) : launch_one<QARL_EPI_NONE>(a, s);
     return launch_qgemm_tile_fp8(a, s);
 }
 
