@@ -14,10 +14,10 @@
 // that run out of step: global-load latency and the VALU work of the expansion are hidden by the
 // other wavefronts' MFMAs rather than by a deep software pipeline.  The kernel is bound by VALU
 // issue next to the MFMAs, so everything outside the k loop is kept short: the expert lookup is a
-// wavefront-level scan, output rows and activation scales wait in LDS, SiLU uses the hardware
+// wavefront-level scan, output rows wait in LDS, SiLU uses the hardware
 // exp2 / rcp, and gate and up meet through one 16-lane row swap.
 //
-// W4A16 group handling is the one described in qgemm_stream.hip: codes become the exact bf16
+// The group handling is the one described in qgemm_stream_w4.hip: codes become the exact bf16
 // values (q+24)/16, every scale group accumulates in its own fp32 accumulator that starts at
 // -1.5 * sum_k x (the sums come from a small pre-pass over the activations, once per call), and
 // is folded in with one FMA by 16*s.
