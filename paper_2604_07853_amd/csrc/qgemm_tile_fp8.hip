@@ -305,6 +305,13 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
             } else {
                 const int ocol0 = nb * kFTN + rho0;
                 const bool tile_ok = ocol0 + 32 <= N;
+                // The 32 x 32 tile (lane: one token, four consecutive columns per register quad) turns through
+                // this wavefront's 4 KiB of the third stage buffer, which the next block's first copies leave
+                // alone, and leaves as 16-byte pieces of whole 128-byte row segments.  Chunks are XOR-swizzled
+                // with the row; the stores are written so that the compiler does not see them (in front of a
+                // visible LDS store it would drain the copies in flight for the next block).
+                unsigned char *ot = smem + 2 * kFStageB + wave * 4096;
+                const uint32_t ot_a = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)ot;
 #pragma unroll
                 for (int a4 = 0; a4 < 4; ++a4) {
                     const int r = 8 * a4 + 4 * h;
@@ -312,17 +319,29 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
                     f32x4 vv;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) vv[i] = acc[ms][nt][4 * a4 + i] * (xs * sw[i]);
-                    if (orow >= 0 && tile_ok) {
+                    const uint32_t dst = ot_a + (uint32_t)(c * 128 + (((2 * a4 + h) ^ (c & 7)) << 4));
+                    asm volatile("ds_write_b128 %0, %1" ::"v"(dst), "v"(vv) : "memory");
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int pass = 0; pass < 4; ++pass) {
+                    const int row = pass * 8 + (lane >> 3);
+                    const f32x4 v4 = *(const f32x4 *)(ot + row * 128 + (lane & 7) * 16);
+                    const int orow_r = s_orow[wm * 64 + ms * 32 + row];
+                    const int col = ocol0 + (((lane & 7) ^ (row & 7)) << 2);
+                    if (orow_r >= 0 && tile_ok) {
+                        unsigned char *dstp = (unsigned char *)p.out + (uint64_t)(uint32_t)orow_r * rstride;
                         if (p.out_f32) {
-                            *(f32x4 *)(orow_base + (ocol0 + r) * 4) = vv;
+                            *(f32x4 *)(dstp + col * 4) = v4;
                         } else {
                             u32x2 o;
-                            o[0] = (uint32_t)f32_to_bf16_hw(vv[0]) | ((uint32_t)f32_to_bf16_hw(vv[1]) << 16);
-                            o[1] = (uint32_t)f32_to_bf16_hw(vv[2]) | ((uint32_t)f32_to_bf16_hw(vv[3]) << 16);
-                            *(u32x2 *)(orow_base + (ocol0 + r) * 2) = o;
+                            o[0] = (uint32_t)f32_to_bf16_hw(v4[0]) | ((uint32_t)f32_to_bf16_hw(v4[1]) << 16);
+                            o[1] = (uint32_t)f32_to_bf16_hw(v4[2]) | ((uint32_t)f32_to_bf16_hw(v4[3]) << 16);
+                            *(u32x2 *)(dstp + col * 2) = o;
                         }
                     }
                 }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             }
         }
     }
