@@ -269,6 +269,28 @@ def main():
                                           "bytes": tb_bytes, "launches": 2}
         del wlm, ws, lp_layer, xp
 
+        # a dense SiLU-gated MLP of a second model shape (hidden 4096, intermediate 12288) through the same calls
+        Hd, Id, Td = 4096, 12288, 4096
+        gud = synth.normal_bf16((1, 2 * Id, Hd), 0.02, seed=70, device=dev)
+        dnd = synth.normal_bf16((1, Hd, Id), 0.02, seed=71, device=dev)
+        qgud, qdnd = q.qarl_quantize_weights(gud), q.qarl_quantize_weights(dnd)
+        del gud, dnd
+        xd = synth.normal_bf16((Td, Hd), 1.0, seed=72, device=dev)
+        offd = torch.tensor([0, Td], dtype=torch.int32, device=dev)
+        ad = torch.empty((Td, Id), dtype=torch.bfloat16, device=dev)
+        yd = torch.empty((Td, Hd), dtype=torch.bfloat16, device=dev)
+        wsd = torch.empty((max(q.qarl_qgemm_workspace_bytes(qgud, Td, Td, q.QARL_EPI_SILU_MUL),
+                               q.qarl_qgemm_workspace_bytes(qdnd, Td, Td, q.QARL_EPI_NONE), 16),), dtype=torch.uint8, device=dev)
+        ms_gud = timed(lambda: q.qarl_qgemm_grouped(qgud, xd, offd, Td, epilogue=q.QARL_EPI_SILU_MUL, out=ad,
+                                                    path=q.QARL_PATH_PREFILL, ws=wsd), 10, 2)
+        ms_dnd = timed(lambda: q.qarl_qgemm_grouped(qdnd, ad, offd, Td, out=yd, path=q.QARL_PATH_PREFILL, ws=wsd), 10, 2)
+        fl_d = 2 * Td * (2 * Id * Hd + Hd * Id)
+        extra["dense_mlp_w4a16_4096x12288_4096tok"] = {
+            "gate_up_ms": round(ms_gud, 4), "down_ms": round(ms_dnd, 4),
+            "TFLOP/s": round(fl_d / (ms_gud + ms_dnd) / 1e9, 1),
+            "frac_mfma_bf16": round(fl_d / (ms_gud + ms_dnd) / 1e9 / MFMA_BF16_PEAK_TF, 4)}
+        del qgud, qdnd, xd, ad, yd, wsd
+
         # FP8 W8A8 layer at 256 and 8192 tokens
         qgu8 = outf
         for T8, path, tag in ((256, q.QARL_PATH_DECODE, "decode"), (8192, q.QARL_PATH_PREFILL, "prefill")):

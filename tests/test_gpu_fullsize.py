@@ -291,3 +291,38 @@ def test_logprob_config3_and_path_mismatch(q, oracle, layer_int4):
     assert float(np.abs(res["seq_w"].cpu().numpy() - wsr).max()) <= 1e-6
     assert float(np.abs(res["seq_w_clipped"].cpu().numpy() - wcr).max()) <= 1e-6
     assert float(np.abs(wsr - 1.0).max()) < 3e-4, wsr
+
+
+def test_dense_mlp_second_model_shape(q, oracle):
+    """A dense (non-MoE) SiLU-gated MLP of a second model shape through the same entry points: hidden 4096,
+    intermediate 12288 (E = 1), 4096 tokens.  K = 4096 is beyond the decode kernel's whole-row LDS tile, so the
+    decode path must refuse it and AUTO must take the MFMA-tiled path.  Codes and scales in full, GEMM outputs on
+    sampled rows (first and last, rows around the 64-row tile borders, a seeded draw)."""
+    H2, I2, T = 4096, 12288, 4096
+    gu = synth.normal_bf16((1, 2 * I2, H2), 0.02, seed=700, device="cuda")
+    dn = synth.normal_bf16((1, H2, I2), 0.02, seed=701, device="cuda")
+    x = synth.normal_bf16((T, H2), 1.0, seed=702, device="cuda")
+    qgu, qdn = q.qarl_quantize_weights(gu), q.qarl_quantize_weights(dn)
+    guc, gus = oracle.quantize_int4(np_bits(gu))
+    dnc, dns = oracle.quantize_int4(np_bits(dn))
+    del gu, dn
+    for qw, c, s, N, K in ((qgu, guc, gus, 2 * I2, H2), (qdn, dnc, dns, H2, I2)):
+        assert np.array_equal(unblock_int4(qw.codes, 1, N, K), c)
+        assert np.array_equal(np_bits(qw.scales).reshape(s.shape), s)
+    off = torch.tensor([0, T], dtype=torch.int32, device="cuda")
+    with pytest.raises(q.QarlError) as ei:
+        q.qarl_qgemm_grouped(qgu, x, off, T, epilogue=q.QARL_EPI_SILU_MUL, path=q.QARL_PATH_DECODE)
+    assert ei.value.status == q.QARL_ERR_UNSUPPORTED
+    a = q.qarl_qgemm_grouped(qgu, x, off, T, epilogue=q.QARL_EPI_SILU_MUL, path=q.QARL_PATH_AUTO)
+    y = q.qarl_qgemm_grouped(qdn, a, off, T, out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_AUTO)
+    rng = np.random.default_rng(703)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 65, 127, 128, T - 65, T - 64, T - 1], rng.integers(0, T, 22)]))
+    sub = np.array([0, rows.size], dtype=np.int32)
+    xr = np_bits(x[torch.tensor(rows, device="cuda")])
+    gu_ref = oracle.qgemm_w4a16(xr, guc, gus, sub)
+    a_ref_bits, a_ref = oracle.silu_mul(gu_ref)
+    a_rows = a[torch.tensor(rows, device="cuda")]
+    assert norm_err_bf16(a_rows.float().cpu().numpy(), a_ref) <= TOL_BF16
+    assert flip_fraction(np_bits(a_rows), a_ref_bits) <= MAX_FLIPS
+    y_ref = oracle.qgemm_w4a16(np_bits(a_rows), dnc, dns, sub)          # on the GPU's own a
+    assert norm_err(y[torch.tensor(rows, device="cuda")].cpu().numpy(), y_ref) <= TOL_F32
