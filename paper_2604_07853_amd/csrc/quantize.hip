@@ -147,13 +147,33 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
     if (row >= rows) return;
     const u32x4 *xr = (const u32x4 *)(x + row * K);
     const int n16 = K / 8;  // 16-byte chunks in the row
+    // rows of up to kKeep * 512 elements stay in registers between the two passes; longer rows are read again
+    constexpr int kKeep = 8;
+    const bool keep = n16 <= kKeep * 64;
+    u32x4 held[kKeep];
     float am = 0.f;
-    for (int c = lane; c < n16; c += 64) {
-        u32x4 v = xr[c];
+    if (keep) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            am = fmaxf(am, fabsf(__uint_as_float(v[i] << 16)));
-            am = fmaxf(am, fabsf(__uint_as_float(v[i] & 0xffff0000u)));
+        for (int u = 0; u < kKeep; ++u) {
+            const int c = lane + 64 * u;
+            held[u] = u32x4{0, 0, 0, 0};
+            if (c < n16) held[u] = xr[c];
+        }
+#pragma unroll
+        for (int u = 0; u < kKeep; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                am = fmaxf(am, fabsf(__uint_as_float(held[u][i] << 16)));
+                am = fmaxf(am, fabsf(__uint_as_float(held[u][i] & 0xffff0000u)));
+            }
+    } else {
+        for (int c = lane; c < n16; c += 64) {
+            u32x4 v = xr[c];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                am = fmaxf(am, fabsf(__uint_as_float(v[i] << 16)));
+                am = fmaxf(am, fabsf(__uint_as_float(v[i] & 0xffff0000u)));
+            }
         }
     }
     am = wave_max(am);
@@ -173,8 +193,7 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
         const float q0 = x * y;
         return copysignf(fmaf(fmaf(-q0, s, x), y, q0), x);   // the sign of x also where the steps end in +0 (x = -0)
     };
-    for (int c = lane; c < n16; c += 64) {
-        u32x4 v = xr[c];
+    auto convert = [&](const u32x4 v, int c) {
         u32x2 o = {0, 0};
         if (s != 0.f) {
             // v_cvt_pk_fp8_f32 rounds to nearest even into OCP e4m3 (subnormals included) exactly like
@@ -195,6 +214,13 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
             o[1] = (uint32_t)w1;
         }
         cr[c] = o;
+    };
+    if (keep) {
+#pragma unroll
+        for (int u = 0; u < kKeep; ++u)
+            if (lane + 64 * u < n16) convert(held[u], lane + 64 * u);
+    } else {
+        for (int c = lane; c < n16; c += 64) convert(xr[c], c);
     }
 }
 
