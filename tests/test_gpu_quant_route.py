@@ -42,7 +42,9 @@ def test_quantize_int4_bit_exact(q, oracle, shape, seed):
     assert np.array_equal(unblock_int4(qw.codes, *shape), codes)
 
 
-@pytest.mark.parametrize("shape,seed", [((2, 64, 2048), 3), ((1, 32, 768), 4), ((1, 32, 128), 5)])
+@pytest.mark.parametrize("shape,seed", [((2, 64, 2048), 3), ((1, 32, 768), 4), ((1, 32, 128), 5),
+                                        ((1, 32, 4096), 6),      # the longest row the kernel keeps in registers
+                                        ((1, 32, 4224), 7), ((1, 32, 8192), 8)])   # longer rows: read twice
 def test_quantize_fp8_bit_exact(q, oracle, shape, seed):
     w = _planted(synth.normal_bf16(shape, 0.02, seed))
     wb = np_bits(w).copy()
