@@ -402,8 +402,9 @@ void oracle_mismatch(const double *lp_learner, const double *lp_sampler,
  *          clip(r, 1 - delta_low, 1 + delta_high) if A <  0,
  *     objective of the response = w~ * r~ * A,
  * and J is the mean over the responses that have tokens.  A response whose ratio leaves its band is
- * masked out of the update: in_band = (lower <= r <= upper), decided on r and the bounds rounded to
- * fp32 (the precision the GPU path compares in).  grad[t] = dJ/d lp_current[t] with w~ held constant
+ * masked out of the update: in_band = (lower <= r <= upper), decided on the ratio itself in fp64
+ * (section 3.2 compares the ratio with the band; a test that sets this against an fp32 implementation
+ * leaves out responses whose ratio lies within rounding distance of a bound).  grad[t] = dJ/d lp_current[t] with w~ held constant
  * (it does not depend on the current policy) = in_band * w~ * A * r / (L * S'), S' = responses with
  * tokens.  An empty response has r = w = w~ = r~ = 1, objective 0, and does not count in S'. */
 void oracle_tbpo(const double *lp_cur, const double *lp_old, const double *lp_smp,
@@ -437,9 +438,8 @@ void oracle_tbpo(const double *lp_cur, const double *lp_old, const double *lp_sm
         const double wt = exp(lw);
         const double lower = adv[s] >= 0.0 ? 1.0 - eps_low : 1.0 - delta_low;
         const double upper = adv[s] >= 0.0 ? 1.0 + eps_high : 1.0 + delta_high;
-        const float r32 = (float)r, lower32 = (float)lower, upper32 = (float)upper;
-        const int inside = (r32 >= lower32) && (r32 <= upper32);
-        const double rt = inside ? r : (r32 < lower32 ? lower : upper);
+        const int inside = (r >= lower) && (r <= upper);
+        const double rt = inside ? r : (r < lower ? lower : upper);
         r_seq[s] = r;
         w_clip[s] = wt;
         r_clip[s] = rt;
