@@ -10,6 +10,9 @@
  *     "host"; the library never frees or keeps them; descriptor structs live on the host;
  *   - the library enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and returns without synchronising the host; it allocates nothing;
+ *   - threads: calls may be made from several host threads at once (no mutable state besides the
+ *     per-thread error text and one-time, per-device kernel set-up that is safe to race), as long as
+ *     calls that run concurrently do not share output or workspace buffers;
  *   - shapes and alignments are checked before any launch; device-side index arrays
  *     (row_map, expert_offsets, sorted_pairs, target) are trusted to be in range;
  *   - bf16 tensors are raw 16-bit patterns; e4m3 is the OCP "fn" flavour whose largest

@@ -23,6 +23,18 @@ int check_hip(hipError_t e, const char *what)
     return QARL_ERR_HIP;
 }
 
+int raise_lds_limit(const void *kernel, LdsLimitOnce &done, const char *what)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) dev = -1;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && (done.devices_done[dev >> 5].load(std::memory_order_acquire) >> (dev & 31) & 1u)) return QARL_OK;
+    int rc = check_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes), what);
+    if (rc) return rc;
+    if (tracked) done.devices_done[dev >> 5].fetch_or(1u << (dev & 31), std::memory_order_release);
+    return QARL_OK;
+}
+
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 static int check_qweight(const qarl_qweight *w, const char *who)

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/qarl.h"
 
 namespace qarl {
@@ -114,6 +116,15 @@ __device__ __forceinline__ void copy_barrier()
 // Host-side error plumbing (api.hip).
 void set_error(const char *fmt, ...);
 int check_hip(hipError_t e, const char *what);
+
+// Kernels that take more than the default 64 KiB of dynamic LDS need their limit raised once per device.
+// Every caller raises it to the same value (the 160 KiB of a gfx950 CU), so concurrent host threads cannot
+// undo each other; `done` (one object per kernel instantiation, zero-initialised) remembers the devices served.
+constexpr int kMaxLdsBytes = 160 * 1024;
+struct LdsLimitOnce {
+    std::atomic<unsigned> devices_done[2];   // bit d of word d / 32: device d (devices >= 64 are set every call)
+};
+int raise_lds_limit(const void *kernel, LdsLimitOnce &done, const char *what);
 
 // Kernel launchers (one per .hip file); all validate nothing: api.hip does.
 int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *scales, hipStream_t s);

@@ -300,14 +300,8 @@ int launch_logprob(const void *h, const void *wlm, const int32_t *target, int T,
         set_error("logprob: grid too large");
         return QARL_ERR_UNSUPPORTED;
     }
-    static bool attr_done = false;
-    if (!attr_done) {
-        int rc = check_hip(hipFuncSetAttribute((const void *)lmhead_lse_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               kLLds),
-                           "hipFuncSetAttribute(lmhead)");
-        if (rc) return rc;
-        attr_done = true;
-    }
+    static LdsLimitOnce once;
+    if (int rc0 = raise_lds_limit((const void *)lmhead_lse_kernel, once, "hipFuncSetAttribute(lmhead)")) return rc0;
     target_logit_kernel<<<dim3((T + 3) / 4), dim3(256), 0, s>>>(p.h, p.w, target, T, H, V, inv_temp, tgt);
     int rc = check_hip(hipGetLastError(), "target_logit_kernel");
     if (rc) return rc;

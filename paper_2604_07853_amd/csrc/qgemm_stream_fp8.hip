@@ -242,14 +242,9 @@ int launch_cfg(const StreamParams &p, hipStream_t s)
         set_error("qgemm (decode path): K=%d needs %zu bytes of LDS per workgroup, more than the 160 KiB of a CU", p.K, lds);
         return QARL_ERR_UNSUPPORTED;
     }
-    static size_t attr_lds = 0;
+    static LdsLimitOnce once;
     auto kern = qgemm_stream_fp8_kernel<EPI, MT, R>;
-    if (lds > attr_lds) {
-        int rc = check_hip(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
-                           "hipFuncSetAttribute(stream fp8)");
-        if (rc) return rc;
-        attr_lds = lds;
-    }
+    if (int rc = raise_lds_limit((const void *)kern, once, "hipFuncSetAttribute(stream fp8)")) return rc;
     const int64_t units = (int64_t)p.E * p.n_slices;
     const int64_t grid = ((units + 7) / 8) * 8 * p.m_split;
     kern<<<dim3((unsigned)grid), dim3(kSThreads), lds, s>>>(p);

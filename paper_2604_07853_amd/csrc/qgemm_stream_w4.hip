@@ -443,14 +443,9 @@ int launch_cfg(const W4Params &p, hipStream_t s)
         set_error("qgemm (decode path): K=%d needs %zu bytes of LDS per workgroup, more than the 160 KiB of a CU", p.K, lds);
         return QARL_ERR_UNSUPPORTED;
     }
-    static size_t attr_lds = 0;
+    static LdsLimitOnce once;
     auto kern = qgemm_stream_w4_kernel<EPI, MT, R>;
-    if (lds > attr_lds) {
-        int rc = check_hip(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
-                           "hipFuncSetAttribute(stream w4)");
-        if (rc) return rc;
-        attr_lds = lds;
-    }
+    if (int rc = raise_lds_limit((const void *)kern, once, "hipFuncSetAttribute(stream w4)")) return rc;
     const int64_t units = (int64_t)p.E << p.slice_sh;
     const int64_t grid = (((units + 7) / 8) * 8) << p.msplit_sh;
     kern<<<dim3((unsigned)grid), dim3(kThreads), lds, s>>>(p);

@@ -353,14 +353,9 @@ static int launch_cfg(const GemmArgs &a, hipStream_t s)
     p.m_slots = (int)slots;
     p.total = (int)total;
     const size_t lds = 2 * ((size_t)kBM * kARowB + kBM * 4);
-    static bool attr_done = false;
+    static LdsLimitOnce once;
     auto kern = qgemm_tile_kernel<EPI, MS>;
-    if (!attr_done) {
-        int rc = check_hip(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
-                           "hipFuncSetAttribute(tile)");
-        if (rc) return rc;
-        attr_done = true;
-    }
+    if (int rc = raise_lds_limit((const void *)kern, once, "hipFuncSetAttribute(tile)")) return rc;
     kern<<<dim3((unsigned)total), dim3(kTileThreads), lds, s>>>(p);
     return check_hip(hipGetLastError(), "qgemm_tile_kernel");
 }

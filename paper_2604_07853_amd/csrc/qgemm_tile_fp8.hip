@@ -385,14 +385,9 @@ static int launch_fp8_cfg(const GemmArgs &a, hipStream_t s)
     }
     p.m_slots = (int)slots;
     p.total = (int)total;
-    static bool attr_done = false;
+    static LdsLimitOnce once;
     auto kern = qgemm_tile_fp8_kernel<EPI>;
-    if (!attr_done) {
-        int rc = check_hip(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kFLds),
-                           "hipFuncSetAttribute(tile fp8)");
-        if (rc) return rc;
-        attr_done = true;
-    }
+    if (int rc = raise_lds_limit((const void *)kern, once, "hipFuncSetAttribute(tile fp8)")) return rc;
     kern<<<dim3((unsigned)total), dim3(kFThreads), kFLds, s>>>(p);
     return check_hip(hipGetLastError(), "qgemm_tile_fp8_kernel");
 }

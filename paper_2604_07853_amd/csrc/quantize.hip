@@ -2,9 +2,11 @@
 //   int4: integer Quant with z = 0, one bf16 scale per 128 consecutive k of a row; codes are
 //         written in 1 KiB blocks of 16 rows x 128 k, the unit the GEMM kernels load;
 //   fp8 : FP Quant with alpha = 448 (e4m3), one fp32 scale per row.
-// Both are HBM-bound streams: 16-byte coalesced loads, the absmax reduced with
-// wavefront shuffles, IEEE fp32 divides so that codes and scales are reproducible
-// bit for bit by any IEEE implementation of the same equations.
+// Both are HBM-bound streams: 16-byte coalesced loads, the absmax reduced with wavefront shuffles.  Codes
+// and scales are DEFINED as the results of IEEE fp32 divides (absmax / 7 or / 448, w / scale), so any IEEE
+// implementation of the equations reproduces them bit for bit; the kernels reach those same bits without a
+// divide per element: a reciprocal multiply with an exact FMA tie test (int4), a reciprocal with one
+// correction step that yields the correctly rounded quotient (fp8).
 #include "common.hpp"
 
 namespace qarl {
@@ -118,23 +120,8 @@ int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *
 }
 
 // ------------------------------------------------------------------- fp8 --
-// e4m3 (OCP fn) nearest-even cast of a finite float, saturating at +-448.
-__device__ __forceinline__ uint32_t e4m3_from_f32(float t)
-{
-    const uint32_t u = __float_as_uint(t);
-    const uint32_t sign = (u >> 24) & 0x80u;
-    const uint32_t a = u & 0x7fffffffu;
-    if (a > 0x7f800000u) return 0x7fu;
-    const float af = __uint_as_float(a);
-    if (af >= 448.f) return sign | 0x7eu;
-    if (af < 0.015625f)  // below the smallest normal 2^-6: fixed quantum 2^-9
-        return sign | (uint32_t)(int)rintf(af * 512.f);
-    // normal: keep 3 mantissa bits, nearest even, carry may bump the exponent
-    const uint32_t r = (a + 0x7ffffu + ((a >> 20) & 1u)) >> 20;
-    return sign | (r - ((127u - 7u) << 3));
-}
-
-// One wavefront per row; the row is read twice (the second read hits cache).
+// One wavefront per row; rows of up to 4096 elements are read once and wait in registers between the absmax
+// pass and the conversion pass, longer rows are read a second time (a cache hit).
 constexpr int kF8Threads = 256;
 
 __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uint16_t *__restrict__ x,

@@ -45,6 +45,10 @@ def norm_err_bf16(got, ref):
     if ref.size == 0:
         return 0.0
     rms = np.sqrt((ref ** 2).mean())
+    # the undiscounted figure first: the bar itself (2e-3) plus the most a rounding to bf16 can add (2^-9 of the
+    # binade top, i.e. below 2^-8 of the value)
+    raw = float((np.abs(got - ref) / (np.abs(ref) + rms + 1e-300)).max())
+    assert raw <= 2e-3 + 2.0 ** -8, "bf16 output off by %.3e before any discount" % raw
     d = np.maximum(np.abs(got - ref) - bf16_half_ulp(ref) * (1 + 1e-9), 0.0)
     return float((d / (np.abs(ref) + rms + 1e-300)).max())
 
@@ -80,4 +84,20 @@ def unblock_int4(codes, E, N, K):
         p = int4_bit_pos(el)
         rot = (w >> np.uint32(p)) | (w << np.uint32((32 - p) % 32)) if p else w   # rotate right by p
         out |= (rot & np.uint32(15)) << np.uint32(4 * el)
+    return out
+
+
+def unblock_int4_torch(codes, E, N, K):
+    """unblock_int4 with torch ops on the tensor's own device (int32 words in, int32 words out, same index
+    permutation of words and bits): for comparisons over many whole layers."""
+    w = codes.contiguous().view(torch.int32).reshape(E * N // 16, K // 128, 4, 16, 4)
+    w = w.permute(0, 3, 1, 2, 4).contiguous().reshape(E, N, K // 8)
+    out = torch.zeros_like(w)
+    for el in range(8):
+        p = int4_bit_pos(el)
+        if p == 0:
+            rot = w
+        else:   # rotate right by p on the 32-bit pattern (arithmetic shifts: mask the sign extension away)
+            rot = ((w >> p) & ((1 << (32 - p)) - 1)) | (w << (32 - p))
+        out |= (rot & 15) << (4 * el)
     return out

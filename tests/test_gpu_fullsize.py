@@ -11,7 +11,7 @@ import pytest
 import torch
 
 from paper_2604_07853_amd import synth
-from gpu_util import np_bits, norm_err, norm_err_bf16, flip_fraction, unblock_int4
+from gpu_util import np_bits, norm_err, norm_err_bf16, flip_fraction, unblock_int4, unblock_int4_torch
 
 pytestmark = pytest.mark.gpu
 
@@ -171,6 +171,30 @@ def test_decode_config5_requantize_then_512_tokens(q, oracle, layer_int4):
         x = synth.normal_bf16((T, H), 1.0, seed=layer_seed + 4, device="cuda")
         lg = synth.router_logits(T, E, seed=layer_seed + 5, device="cuda")
         _w4a16_stages(q, oracle, L, x, lg, T, q.QARL_PATH_DECODE, seed=layer_seed + 6)
+
+
+def test_config5_all_48_layers_codes_and_scales(q, oracle):
+    """Config 5, the weight pass over the whole stack: every one of the 48 layers is drawn, moved by N(0, 1e-4),
+    re-quantized into the buffers that held the previous layer's codes, and compared with the oracle's codes and
+    scales bit for bit (the GEMM stages run on two layers in the test above)."""
+    qgu = q.QWeight.empty(q.QARL_W4A16_G128, E, 2 * I, H)
+    qdn = q.QWeight.empty(q.QARL_W4A16_G128, E, H, I)
+    for layer in range(48):
+        gu, dn = synth.expert_weights(E, H, I, seed=5000 + 2 * layer, device="cuda")
+        gu2 = synth.perturb(gu, 1e-4, 6000 + 2 * layer)
+        dn2 = synth.perturb(dn, 1e-4, 6001 + 2 * layer)
+        del gu, dn
+        q.qarl_quantize_weights(gu2, out=qgu)
+        q.qarl_quantize_weights(dn2, out=qdn)
+        for qw, m, N, K in ((qgu, gu2, 2 * I, H), (qdn, dn2, H, I)):
+            c, s = oracle.quantize_int4(np_bits(m))
+            got = unblock_int4_torch(qw.codes, E, N, K)
+            assert torch.equal(got, torch.from_numpy(c.view(np.int32)).cuda()), layer
+            assert torch.equal(qw.scales.view(torch.int16).reshape(s.shape),
+                               torch.from_numpy(s.view(np.int16)).cuda()), layer
+        del gu2, dn2
+        if layer % 8 == 7:
+            print("config 5: layers 0..%d identical" % layer, flush=True)
 
 
 @pytest.mark.parametrize("T,path", [(256, 1), (8192, 2)])

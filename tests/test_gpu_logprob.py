@@ -75,3 +75,18 @@ def test_fused_comparison_outputs(q, oracle):
     assert np.abs(res["delta"].cpu().numpy() - d).max() <= 2 * TOL_LP
     assert np.allclose(res["seq_w"].cpu().numpy(), ws, atol=2 * TOL_LP)
     assert np.allclose(res["seq_w_clipped"].cpu().numpy(), wc, atol=2 * TOL_LP)
+
+
+def test_target_outside_vocabulary_gives_nan_for_that_token_only(q, oracle):
+    T, H, V = 70, 128, 600
+    h = synth.normal_bf16((T, H), 1.0, seed=21)
+    w = synth.normal_bf16((V, H), 0.3, seed=22)
+    tg = synth.targets(T, V, seed=23)
+    ref = oracle.token_logprob(np_bits(h), np_bits(w), tg.numpy(), 1.0)
+    bad = tg.clone()
+    bad[3], bad[40], bad[69] = -1, V, 2 ** 31 - 1
+    got = q.qarl_token_logprob(h.cuda(), w.cuda(), bad.cuda())["logprob"].cpu().numpy()
+    assert np.isnan(got[[3, 40, 69]]).all()
+    ok = np.ones(T, dtype=bool)
+    ok[[3, 40, 69]] = False
+    assert np.abs(got[ok].astype(np.float64) - ref[ok]).max() <= TOL_LP

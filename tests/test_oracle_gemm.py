@@ -128,3 +128,44 @@ def test_moe_layer_matches_dense_torch_reference(oracle):
             a = (torch.nn.functional.silu(z[:Ii]) * z[Ii:]).to(torch.bfloat16).double()
             out[t] += wsel[j] * (Wdn[e] @ a)
     assert np.allclose(res["out"], out.numpy(), rtol=1e-9, atol=1e-12)
+
+
+def test_fp8_moe_layer_matches_dense_torch_reference(oracle):
+    """The whole FP8 W8A8 layer (eq. (2): per-token e4m3 activations, per-channel e4m3 weights) against a dense
+    float64 torch evaluation that never groups tokens and takes its e4m3 casts from torch's own float8 type:
+    out[t] = sum_j w_j * s_a s_d (D_q a_q), a = bf16(silu(g) * u), (g, u) = s_x s_w (W_q x_q)."""
+    E, Hh, Ii, T, k = 8, 256, 128, 20, 3
+    gu, dn = synth.expert_weights(E, Hh, Ii, seed=13)
+    guq, gus = oracle.quantize_fp8_rows(synth.bits(gu))
+    dnq, dns = oracle.quantize_fp8_rows(synth.bits(dn))
+    x = synth.normal_bf16((T, Hh), 1.0, seed=14)
+    lg = synth.router_logits(T, E, seed=15)
+    res = oracle.moe_ffn_fp8(synth.bits(x), synth.bits(lg), guq, gus, dnq, dns, topk=k)
+
+    def f8(codes):
+        return torch.from_numpy(np.ascontiguousarray(codes)).view(torch.float8_e4m3fn).double()
+
+    def quant_row(v_bf16):                      # FP Quant of section 2.2 on one bf16 row, fp32 arithmetic
+        v = v_bf16.float()
+        s = v.abs().max() / torch.tensor(448.0)
+        if s == 0:
+            return torch.zeros_like(v).double(), 0.0
+        return (v / s).clamp(-448, 448).to(torch.float8_e4m3fn).double(), float(s)
+
+    Wgu, Wdn = f8(guq), f8(dnq)
+    sgu, sdn = torch.from_numpy(gus).double(), torch.from_numpy(dns).double()
+    p = torch.softmax(lg.double(), dim=1)
+    out = torch.zeros(T, Hh, dtype=torch.float64)
+    for t in range(T):
+        ids = res["ids"][t]
+        wsel = p[t, ids.tolist()]
+        wsel = wsel / wsel.sum()
+        xq, sx = quant_row(x[t])
+        for j, e in enumerate(ids):
+            z = sx * sgu[e] * (Wgu[e] @ xq)
+            a = (torch.nn.functional.silu(z[:Ii]) * z[Ii:]).to(torch.bfloat16)
+            aq, sa = quant_row(a)
+            out[t] += wsel[j] * (sa * sdn[e] * (Wdn[e] @ aq))
+    assert np.allclose(res["out"], out.numpy(), rtol=1e-9, atol=1e-12)
+    # the stages it returns are the ones the stage-wise GPU comparison reads
+    assert res["aq"].shape == (T * k, Ii) and res["sa"].shape == (T * k,) and res["xq"].shape == (T, Hh)
