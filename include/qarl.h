@@ -175,6 +175,23 @@ int qarl_token_logprob(const void *h_bf16, const void *w_lm_bf16, const int32_t 
                        float tis_cap_c, float *delta, float *seq_w, float *seq_w_clipped, void *ws,
                        size_t ws_bytes, void *stream);
 
+/* qarl_token_logprob for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops that score the tokens of a decode step, harnesses that forbid hipMalloc.
+ * Same arguments, results and errors as qarl_token_logprob without `ws`: the partial maxima and sums of the
+ * vocabulary blocks go to an array built into the library's device code, qarl_token_logprob_static_limit()
+ * bytes (4 MiB) on every GPU the library runs on, held until the process ends.  The call allocates and frees
+ * nothing.  A call whose partials exceed the limit (qarl_logprob_workspace_bytes(T, H, V) > limit; at V = 151936
+ * that is T > 881) returns QARL_ERR_WORKSPACE.  The array keeps the last call's contents; every element a
+ * call reads it has written before, so nothing needs clearing.  All calls on one GPU share the array: calls
+ * that overlap on one GPU (different streams or threads) race and must be serialised by the caller.  The
+ * array's address on a device is looked up on the first call made with that device current (make that call
+ * outside a graph capture). */
+int qarl_token_logprob_static(const void *h_bf16, const void *w_lm_bf16, const int32_t *target, int T, int H,
+                              int V, float inv_temperature, float *logprob, const float *ref_logprob,
+                              const int32_t *seq_offsets, int S, float tis_cap_c, float *delta, float *seq_w,
+                              float *seq_w_clipped, void *stream);
+size_t qarl_token_logprob_static_limit(void);
+
 /* The comparison half of qarl_token_logprob on two existing log-prob streams (learner
  * and sampler): delta, token weight w = exp(delta) (eq. (3)), seq_w and seq_w_clipped as
  * above.  Any output may be NULL. */

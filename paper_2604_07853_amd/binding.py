@@ -20,9 +20,11 @@ QARL_PATH_AUTO, QARL_PATH_DECODE, QARL_PATH_PREFILL = 0, 1, 2
 QARL_EPI_NONE, QARL_EPI_SILU_MUL, QARL_EPI_COMBINE = 0, 1, 2
 QARL_OUT_BF16, QARL_OUT_F32 = 0, 1
 
+# the first four return a string or a size, the rest a qarl_status
 EXPORTS = ["qarl_last_error", "qarl_qgemm_workspace_bytes", "qarl_logprob_workspace_bytes",
-           "qarl_quantize_weights", "qarl_quantize_rows_fp8", "qarl_moe_route", "qarl_qgemm_grouped",
-           "qarl_qgemm_routed", "qarl_token_logprob", "qarl_logprob_mismatch", "qarl_tbpo_objective"]
+           "qarl_token_logprob_static_limit", "qarl_quantize_weights", "qarl_quantize_rows_fp8", "qarl_moe_route", "qarl_qgemm_grouped",
+           "qarl_qgemm_routed", "qarl_token_logprob", "qarl_logprob_mismatch", "qarl_tbpo_objective",
+           "qarl_token_logprob_static"]
 
 
 class QarlError(RuntimeError):
@@ -67,7 +69,12 @@ def lib():
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.qarl_tbpo_objective.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
                                           C.c_float, C.c_float, C.c_float, C.c_float, C.c_float] + [C.c_void_p] * 8
-        for name in EXPORTS[3:]:
+        L.qarl_token_logprob_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
+                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
+                                                C.c_void_p, C.c_void_p, C.c_void_p]
+        L.qarl_token_logprob_static_limit.restype = C.c_size_t
+        L.qarl_token_logprob_static_limit.argtypes = []
+        for name in EXPORTS[4:]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -228,6 +235,19 @@ def qarl_token_logprob(h, w_lm, target, inv_temperature=1.0, ref_logprob=None, s
                                     _ptr(ref_logprob), _ptr(seq_offsets), S, tis_cap_c, _ptr(delta), _ptr(seq_w),
                                     _ptr(seq_wc), _ptr(ws), ws.numel(), _stream()))
     return dict(logprob=lp, delta=delta, seq_w=seq_w, seq_w_clipped=seq_wc)
+
+
+def qarl_token_logprob_static_limit():
+    return lib().qarl_token_logprob_static_limit()
+
+
+def qarl_token_logprob_static(h, w_lm, target, logprob, inv_temperature=1.0):
+    """qarl_token_logprob on the library's built-in scratch; writes the caller's `logprob` [T] and allocates nothing."""
+    T, H = h.shape
+    V = w_lm.shape[0]
+    _check(lib().qarl_token_logprob_static(_ptr(h), _ptr(w_lm), _ptr(target), T, H, V, inv_temperature, _ptr(logprob),
+                                           None, None, 0, 2.0, None, None, None, _stream()))
+    return logprob
 
 
 def qarl_logprob_mismatch(lp_learner, lp_sampler, seq_offsets=None, tis_cap_c=2.0):

@@ -29,7 +29,12 @@ int raise_lds_limit(const void *kernel, LdsLimitOnce &done, const char *what)
     if (hipGetDevice(&dev) != hipSuccess) dev = -1;
     const bool tracked = dev >= 0 && dev < 64;
     if (tracked && (done.devices_done[dev >> 5].load(std::memory_order_acquire) >> (dev & 31) & 1u)) return QARL_OK;
-    int rc = check_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes), what);
+    // the dynamic part may fill what the kernel's static LDS leaves of the CU's 160 KiB
+    hipFuncAttributes fa;
+    int rc = check_hip(hipFuncGetAttributes(&fa, kernel), what);
+    if (rc) return rc;
+    const int room = kMaxLdsBytes - (int)fa.sharedSizeBytes;
+    rc = check_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, room), what);
     if (rc) return rc;
     if (tracked) done.devices_done[dev >> 5].fetch_or(1u << (dev & 31), std::memory_order_release);
     return QARL_OK;
@@ -466,5 +471,31 @@ int qarl_token_logprob(const void *h_bf16, const void *w_lm_bf16, const int32_t 
                                      seq_w_clipped, stream);
     return QARL_OK;
 }
+
+int qarl_token_logprob_static(const void *h_bf16, const void *w_lm_bf16, const int32_t *target, int T, int H, int V,
+                              float inv_temperature, float *logprob, const float *ref_logprob,
+                              const int32_t *seq_offsets, int S, float tis_cap_c, float *delta, float *seq_w,
+                              float *seq_w_clipped, void *stream)
+{
+    if (T < 0 || H <= 0 || V <= 0) {
+        set_error("qarl_token_logprob_static: T >= 0, H > 0, V > 0 required");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (T == 0) return QARL_OK;
+    const size_t need = qarl_logprob_workspace_bytes(T, H, V);
+    if (need > kLogprobScratchBytes) {
+        set_error("qarl_token_logprob_static: T=%d tokens over V=%d need %zu bytes of partial results, more than the "
+                  "library's %zu bytes of built-in scratch; use qarl_token_logprob with a caller workspace",
+                  T, V, need, (size_t)kLogprobScratchBytes);
+        return QARL_ERR_WORKSPACE;
+    }
+    void *ws = nullptr;
+    int rc = logprob_static_scratch(&ws);
+    if (rc) return rc;
+    return qarl_token_logprob(h_bf16, w_lm_bf16, target, T, H, V, inv_temperature, logprob, ref_logprob, seq_offsets,
+                              S, tis_cap_c, delta, seq_w, seq_w_clipped, ws, kLogprobScratchBytes, stream);
+}
+
+size_t qarl_token_logprob_static_limit(void) { return kLogprobScratchBytes; }
 
 }  // extern "C"

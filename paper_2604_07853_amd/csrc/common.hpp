@@ -118,7 +118,7 @@ void set_error(const char *fmt, ...);
 int check_hip(hipError_t e, const char *what);
 
 // Kernels that take more than the default 64 KiB of dynamic LDS need their limit raised once per device.
-// Every caller raises it to the same value (the 160 KiB of a gfx950 CU), so concurrent host threads cannot
+// Every caller raises it to the same value (the 160 KiB of a gfx950 CU less the kernel's static LDS), so concurrent host threads cannot
 // undo each other; `done` (one object per kernel instantiation, zero-initialised) remembers the devices served.
 constexpr int kMaxLdsBytes = 160 * 1024;
 struct LdsLimitOnce {
@@ -168,6 +168,9 @@ int launch_combine(const float *y_pair_order, const float *w, int T, int topk, i
 int launch_logprob(const void *h, const void *wlm, const int32_t *target, int T, int H, int V,
                    float inv_temp, float *logprob, void *ws, hipStream_t s);
 size_t logprob_ws_bytes(int T, int H, int V);
+// Device address, on the current device, of the library's own file-scope scratch array (kLogprobScratchBytes).
+constexpr size_t kLogprobScratchBytes = (size_t)4 << 20;
+int logprob_static_scratch(void **ptr);
 int launch_fill_f32(float *p, int n, float v, hipStream_t s);
 int launch_tbpo(const float *lp_cur, const float *lp_old, const float *lp_smp, const int32_t *seq_offsets, int S,
                 const float *adv, float eps_low, float eps_high, float delta_low, float delta_high, float c,

@@ -312,4 +312,34 @@ int launch_logprob(const void *h, const void *wlm, const int32_t *target, int T,
     return check_hip(hipGetLastError(), "lse_finalize_kernel");
 }
 
+// ---- the library's own scratch for callers that cannot allocate.  One copy of the array exists on every GPU
+// the library's code object is loaded on, at that GPU's own address.  In host code the array's NAME is only a
+// handle for the symbol lookup below, never a device address: everything that touches the memory (kernel
+// arguments, copies, fills) takes the pointer this function returns.
+static __device__ __align__(256) unsigned char scratch[kLogprobScratchBytes];
+static std::atomic<void *> g_scratch_ptr[64];   // per device, filled on the first call with that device current
+
+int logprob_static_scratch(void **ptr)
+{
+    int dev = -1;
+    int rc = check_hip(hipGetDevice(&dev), "hipGetDevice");
+    if (rc) return rc;
+    if (dev < 0 || dev >= 64) {
+        set_error("logprob (library scratch): device index %d outside the table of 64", dev);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        rc = check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (rc) return rc;
+        if (!p) {
+            set_error("logprob (library scratch): symbol lookup returned a null address");
+            return QARL_ERR_HIP;
+        }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return QARL_OK;
+}
+
 }  // namespace qarl
