@@ -2,8 +2,8 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras] [--no-cpu]
 
-A step is one pass of the decode-shaped W4A16 MoE layer (route -> group -> gate_up GEMM with
-SiLU*mul -> down GEMM -> weighted combine) over one batch of 256 synthetic tokens with
+A step is one pass of the decode-shaped W4A16 MoE layer (route -> gate_up GEMM with SiLU*mul ->
+down GEMM -> weighted combine; the GEMMs take the router's ids directly) over one batch of 256 synthetic tokens with
 Qwen3-30B-A3B expert shapes (128 experts, hidden 2048, intermediate 768, top-8), every input
 already resident in HBM.  The quantized weights rotate over several distinct copies so that the
 256 MB last-level cache cannot serve a 311 MB layer twice.  Prints ONE JSON line: the decode
@@ -25,9 +25,12 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TF = 2500.0
 MFMA_FP8_PEAK_TF = 5000.0
 # HBM bytes per gate_up launch of the headline step from two counter runs (2.000 x FETCH_SIZE + 1.000 x WRITE_SIZE,
-# the factors a plain copy kernel of known size gives): profiles/qgemm_stream_decode256_hbm_traffic.txt.
-# Counters cannot be read from inside this process, so the figure is stored; it belongs to the 256-token workload.
+# the factors a plain copy kernel of known size gives).  Counters cannot be read from inside this process, so the
+# figure is stored with the summary it comes from; it belongs to the 256-token workload and to the kernel as it
+# stood when that summary was taken (the gate_up launch of qgemm_stream_w4.hip has not changed since).
 GATE_UP_TRAFFIC_BYTES = 220271616
+GATE_UP_TRAFFIC_SOURCE = "profiles/qgemm_stream_decode256_hbm_traffic.txt"
+MIN_EVENT_LAUNCHES = 32   # gate_up launches bracketed by events, whatever --steps is
 
 
 def weight_bytes_w4a16(E, N, K):
@@ -135,6 +138,12 @@ def main():
     t1.record()
     torch.cuda.synchronize()
     ms_step = t0.elapsed_time(t1) / args.steps
+    timed_in_region = len(gu_events)
+    k = 0
+    while len(gu_events) < MIN_EVENT_LAUNCHES:      # a short run: further bracketed launches behind the timed region,
+        step(record=(k % 2 == 1))                   # every other step, in the same rotation over the weight copies
+        k += 1
+    torch.cuda.synchronize()
     if args.calibrate:
         ca = torch.ones((64 << 20,), dtype=torch.float32, device=dev)
         cb = torch.empty_like(ca)
@@ -142,7 +151,8 @@ def main():
             torch.mul(ca, 1.0, out=cb)
         torch.cuda.synchronize()
         del ca, cb
-    ms_gu = float(np.mean([a.elapsed_time(b) for a, b in gu_events]))
+    gu_times = np.array([a.elapsed_time(b) for a, b in gu_events])
+    ms_gu = float(gu_times.mean())
 
     # algorithmic bytes of a step: every expert's codes + scales once, logits, x, a (written + read), out
     active = int(torch.unique(layers[0].routing.ids).numel())
@@ -173,7 +183,12 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "qgemm_stream_w4_kernel<SILU_MUL> (gate_up)",
                      "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": GATE_UP_TRAFFIC_BYTES,
-                     "bytes_per_launch": gu_bytes, "ms_per_launch": round(ms_gu, 5), "launches_timed": len(gu_events),
+                     "traffic_source": GATE_UP_TRAFFIC_SOURCE,
+                     "bytes_per_launch": gu_bytes, "ms_per_launch": round(ms_gu, 5),
+                     "ms_per_launch_median": round(float(np.median(gu_times)), 5), "launches_timed": len(gu_events),
+                     "launches_timed_inside_region": timed_in_region,
+                     "note": "event brackets add about 3 us to a launch; the kernel trace under profiles/ has the "
+                             "kernel's own duration",
                      "step_frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
     }
 
@@ -291,19 +306,30 @@ def main():
             "frac_mfma_bf16": round(fl_d / (ms_gud + ms_dnd) / 1e9 / MFMA_BF16_PEAK_TF, 4)}
         del qgud, qdnd, xd, ad, yd, wsd
 
-        # FP8 W8A8 layer at 256 and 8192 tokens
+        # FP8 W8A8 layer at 256 and 8192 tokens: the whole layer, and the two grouped GEMM launches on their own
         qgu8 = outf
         for T8, path, tag in ((256, q.QARL_PATH_DECODE, "decode"), (8192, q.QARL_PATH_PREFILL, "prefill")):
             x8 = synth.normal_bf16((T8, H), 1.0, seed=50, device=dev)
             lg8 = synth.router_logits(T8, E, seed=51, device=dev)
             l8 = q.MoELayer(qgu8, qdn8, T8, TOPK, path, dev)
             ms8 = timed(lambda: l8.forward(x8, lg8), 20, 3)
+            r8, M8 = l8.routing, T8 * TOPK
+            ms8_gu = timed(lambda: q.qarl_qgemm_grouped(qgu8, l8.xq, r8.offsets, M8, row_map=r8.tokens, x_scales=l8.sx,
+                                                        epilogue=q.QARL_EPI_SILU_MUL, out=l8.a, path=path), 20, 3)
+            y8 = torch.empty((M8, H), dtype=torch.float32, device=dev)
+            ms8_dn = timed(lambda: q.qarl_qgemm_grouped(qdn8, l8.aq, r8.offsets, M8, x_scales=l8.sa, out=y8,
+                                                        out_dtype=q.QARL_OUT_F32, path=path), 20, 3)
+            del y8
             b8 = weight_bytes_fp8(E, 2 * I, H) + weight_bytes_fp8(E, H, I)
             f8 = synth.flops_moe(T8)
-            extra["fp8_%s_%dtok" % (tag, T8)] = {"layer_ms": round(ms8, 4), "weight_GB/s": round(b8 / ms8 / 1e6, 1),
-                                                 "frac_hbm": round(b8 / ms8 / 1e6 / HBM_PEAK_GBS, 4),
-                                                 "TFLOP/s": round(f8 / ms8 / 1e9, 1),
-                                                 "frac_mfma_fp8": round(f8 / ms8 / 1e9 / MFMA_FP8_PEAK_TF, 4)}
+            extra["fp8_%s_%dtok" % (tag, T8)] = {
+                "layer_ms": round(ms8, 4), "gate_up_ms": round(ms8_gu, 4), "down_ms": round(ms8_dn, 4),
+                "weight_GB/s": round(b8 / ms8 / 1e6, 1), "frac_hbm": round(b8 / ms8 / 1e6 / HBM_PEAK_GBS, 4),
+                "gemm_weight_GB/s": round(b8 / (ms8_gu + ms8_dn) / 1e6, 1),
+                "gemm_frac_hbm": round(b8 / (ms8_gu + ms8_dn) / 1e6 / HBM_PEAK_GBS, 4),
+                "TFLOP/s": round(f8 / ms8 / 1e9, 1), "frac_mfma_fp8": round(f8 / ms8 / 1e9 / MFMA_FP8_PEAK_TF, 4),
+                "gemm_TFLOP/s": round(f8 / (ms8_gu + ms8_dn) / 1e9, 1),
+                "gemm_frac_mfma_fp8": round(f8 / (ms8_gu + ms8_dn) / 1e9 / MFMA_FP8_PEAK_TF, 4)}
             del l8
         del qgu8, qdn8, outf, outq
 
