@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--event-every", type=int, default=8,
                     help="bracket the dominant launch with HIP events on every N-th timed step")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--extras", default="all",
+                    help="comma-separated subset of the other rows to time: quantize, prefill (with the LM head and the "
+                         "sequence objective), dense, fp8, stack; default all")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--sweep-layers", type=int, default=48)
     ap.add_argument("--calibrate", action="store_true",
@@ -213,7 +216,9 @@ def main():
     # ---- the other rows of the path, each timed on its own
     if not args.no_extras:
         extra = {}
-        # (a1) int4 re-quantization of one layer's masters
+        want = set(args.extras.split(","))
+        on = lambda name: "all" in want or name in want
+        # (a1) int4 re-quantization of one layer's masters (the fp8 copies below feed the fp8 rows)
         gu, dn = synth.expert_weights(E, H, I, seed=5000, device=dev)
         outq = q.QWeight.empty(q.QARL_W4A16_G128, E, 2 * I, H, dev)
         ms = timed(lambda: q.qarl_quantize_weights(gu, out=outq), 20, 3)
@@ -228,146 +233,167 @@ def main():
         qdn8 = q.qarl_quantize_weights(dn, q.QARL_FP8_E4M3_CH)
         del gu, dn
 
-        # (a6-a9) prefill / training-forward shape, W4A16: 8 x 2048 tokens, Zipf-skewed router
-        Tp = 16384
-        xp = synth.normal_bf16((Tp, H), 1.0, seed=30, device=dev)
-        lgp = synth.router_logits(Tp, E, seed=31, device=dev, zipf_s=1.1)
-        lp_layer = q.MoELayer(layers[0].gu, layers[0].dn, Tp, TOPK, q.QARL_PATH_PREFILL, dev)
-        ms_all = timed(lambda: lp_layer.forward(xp, lgp), 10, 2)
-        r = lp_layer.routing
-        Mp = Tp * TOPK
-        ms_gu_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.gu, xp, r.offsets, Mp, row_map=r.tokens,
-                                                     epilogue=q.QARL_EPI_SILU_MUL, out=lp_layer.a,
-                                                     path=q.QARL_PATH_PREFILL, ws=lp_layer.ws), 10, 2)
-        ybuf = torch.empty((Mp, H), dtype=torch.float32, device=dev)
-        ms_dn_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.dn, lp_layer.a, r.offsets, Mp, out=ybuf,
-                                                     out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_PREFILL,
-                                                     ws=lp_layer.ws), 10, 2)
-        del ybuf
-        fl_gu, fl_dn = 2 * Mp * 2 * I * H, 2 * Mp * H * I
-        extra["prefill_w4a16_16384tok_zipf"] = {
-            "layer_ms": round(ms_all, 4), "gate_up_ms": round(ms_gu_p, 4), "down_ms": round(ms_dn_p, 4),
-            "gemm_TFLOP/s": round((fl_gu + fl_dn) / (ms_gu_p + ms_dn_p) / 1e9, 1),
-            "gemm_frac_mfma_bf16": round((fl_gu + fl_dn) / (ms_gu_p + ms_dn_p) / 1e9 / MFMA_BF16_PEAK_TF, 4),
-            "layer_TFLOP/s": round((fl_gu + fl_dn) / ms_all / 1e9, 1),
-            "max_expert_rows": int(r.counts.max()), "min_expert_rows": int(r.counts.min())}
-        lgu = synth.router_logits(Tp, E, seed=32, device=dev)
-        ms_all_u = timed(lambda: lp_layer.forward(xp, lgu), 10, 2)
-        extra["prefill_w4a16_16384tok_uniform"] = {"layer_ms": round(ms_all_u, 4),
-                                                   "layer_TFLOP/s": round((fl_gu + fl_dn) / ms_all_u / 1e9, 1)}
+        if on("prefill"):
+            # (a6-a9) prefill / training-forward shape, W4A16: 8 x 2048 tokens, Zipf-skewed router
+            Tp = 16384
+            xp = synth.normal_bf16((Tp, H), 1.0, seed=30, device=dev)
+            lgp = synth.router_logits(Tp, E, seed=31, device=dev, zipf_s=1.1)
+            lp_layer = q.MoELayer(layers[0].gu, layers[0].dn, Tp, TOPK, q.QARL_PATH_PREFILL, dev)
+            ms_all = timed(lambda: lp_layer.forward(xp, lgp), 10, 2)
+            r = lp_layer.routing
+            Mp = Tp * TOPK
+            ms_gu_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.gu, xp, r.offsets, Mp, row_map=r.tokens,
+                                                         epilogue=q.QARL_EPI_SILU_MUL, out=lp_layer.a,
+                                                         path=q.QARL_PATH_PREFILL, ws=lp_layer.ws), 10, 2)
+            ybuf = torch.empty((Mp, H), dtype=torch.float32, device=dev)
+            ms_dn_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.dn, lp_layer.a, r.offsets, Mp, out=ybuf,
+                                                         out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_PREFILL,
+                                                         ws=lp_layer.ws), 10, 2)
+            del ybuf
+            fl_gu, fl_dn = 2 * Mp * 2 * I * H, 2 * Mp * H * I
+            extra["prefill_w4a16_16384tok_zipf"] = {
+                "layer_ms": round(ms_all, 4), "gate_up_ms": round(ms_gu_p, 4), "down_ms": round(ms_dn_p, 4),
+                "gemm_TFLOP/s": round((fl_gu + fl_dn) / (ms_gu_p + ms_dn_p) / 1e9, 1),
+                "gemm_frac_mfma_bf16": round((fl_gu + fl_dn) / (ms_gu_p + ms_dn_p) / 1e9 / MFMA_BF16_PEAK_TF, 4),
+                "layer_TFLOP/s": round((fl_gu + fl_dn) / ms_all / 1e9, 1),
+                "max_expert_rows": int(r.counts.max()), "min_expert_rows": int(r.counts.min())}
+            lgu = synth.router_logits(Tp, E, seed=32, device=dev)
+            ms_all_u = timed(lambda: lp_layer.forward(xp, lgu), 10, 2)
+            extra["prefill_w4a16_16384tok_uniform"] = {"layer_ms": round(ms_all_u, 4),
+                                                       "layer_TFLOP/s": round((fl_gu + fl_dn) / ms_all_u / 1e9, 1)}
 
-        # (a10, a11) LM head + log-prob on the layer's output
-        V = synth.V
-        wlm = synth.normal_bf16((V, H), 0.02, seed=40, device=dev)
-        tg = synth.targets(Tp, V, seed=41, device=dev)
-        ws = torch.empty((q.qarl_logprob_workspace_bytes(Tp, H, V),), dtype=torch.uint8, device=dev)
-        hh = lp_layer.out
-        ms_lp = timed(lambda: q.qarl_token_logprob(hh, wlm, tg, ws=ws), 3, 1)
-        fl_lp = 2 * Tp * H * V
-        extra["lm_head_logprob_16384x151936"] = {"ms": round(ms_lp, 3), "TFLOP/s": round(fl_lp / ms_lp / 1e9, 1),
-                                                 "frac_mfma_bf16": round(fl_lp / ms_lp / 1e9 / MFMA_BF16_PEAK_TF, 4)}
-        # sequence-level surrogate (section 3.2) on the log-probs of that configuration: 8 responses x 2048 tokens.
-        # Two small launches over 0.26 MB: launch-bound, reported as time per call.
-        Sq, Lq = 8, Tp // 8
-        g = torch.Generator(device=dev)
-        g.manual_seed(60)
-        lp_o = -torch.rand((Tp,), generator=g, device=dev) * 5 - 0.01
-        lp_c = lp_o + torch.randn((Tp,), generator=g, device=dev) * 1e-3
-        lp_s = lp_o + torch.randn((Tp,), generator=g, device=dev) * 0.05
-        so = torch.arange(Sq + 1, dtype=torch.int32, device=dev) * Lq
-        adv = torch.randn((Sq,), generator=g, device=dev)
-        tb_out = q.qarl_tbpo_objective(lp_c, lp_o, lp_s, so, adv, 1.0, 0.0004, 0.0003, 0.0007, 2.0)
-        ms_tb = timed(lambda: q.qarl_tbpo_objective(lp_c, lp_o, lp_s, so, adv, 1.0, 0.0004, 0.0003, 0.0007, 2.0,
-                                                    out=tb_out), 50, 5)
-        tb_bytes = 4 * Tp * 4
-        extra["tbpo_objective_8x2048"] = {"ms": round(ms_tb, 4), "GB/s": round(tb_bytes / ms_tb / 1e6, 1),
-                                          "bytes": tb_bytes, "launches": 2}
-        del wlm, ws, lp_layer, xp
+            # (a10, a11) LM head + log-prob on the layer's output
+            V = synth.V
+            wlm = synth.normal_bf16((V, H), 0.02, seed=40, device=dev)
+            tg = synth.targets(Tp, V, seed=41, device=dev)
+            ws = torch.empty((q.qarl_logprob_workspace_bytes(Tp, H, V),), dtype=torch.uint8, device=dev)
+            hh = lp_layer.out
+            ms_lp = timed(lambda: q.qarl_token_logprob(hh, wlm, tg, ws=ws), 3, 1)
+            fl_lp = 2 * Tp * H * V
+            extra["lm_head_logprob_16384x151936"] = {"ms": round(ms_lp, 3), "TFLOP/s": round(fl_lp / ms_lp / 1e9, 1),
+                                                     "frac_mfma_bf16": round(fl_lp / ms_lp / 1e9 / MFMA_BF16_PEAK_TF, 4)}
+            # sequence-level surrogate (section 3.2) on the log-probs of that configuration: 8 responses x 2048 tokens.
+            # Two small launches over 0.26 MB: launch-bound, reported as time per call.
+            Sq, Lq = 8, Tp // 8
+            g = torch.Generator(device=dev)
+            g.manual_seed(60)
+            lp_o = -torch.rand((Tp,), generator=g, device=dev) * 5 - 0.01
+            lp_c = lp_o + torch.randn((Tp,), generator=g, device=dev) * 1e-3
+            lp_s = lp_o + torch.randn((Tp,), generator=g, device=dev) * 0.05
+            so = torch.arange(Sq + 1, dtype=torch.int32, device=dev) * Lq
+            adv = torch.randn((Sq,), generator=g, device=dev)
+            tb_out = q.qarl_tbpo_objective(lp_c, lp_o, lp_s, so, adv, 1.0, 0.0004, 0.0003, 0.0007, 2.0)
+            ms_tb = timed(lambda: q.qarl_tbpo_objective(lp_c, lp_o, lp_s, so, adv, 1.0, 0.0004, 0.0003, 0.0007, 2.0,
+                                                        out=tb_out), 50, 5)
+            tb_bytes = 4 * Tp * 4
+            extra["tbpo_objective_8x2048"] = {"ms": round(ms_tb, 4), "GB/s": round(tb_bytes / ms_tb / 1e6, 1),
+                                              "bytes": tb_bytes, "launches": 2}
+            del wlm, ws, lp_layer, xp
 
-        # a dense SiLU-gated MLP of a second model shape (hidden 4096, intermediate 12288) through the same calls
-        Hd, Id, Td = 4096, 12288, 4096
-        gud = synth.normal_bf16((1, 2 * Id, Hd), 0.02, seed=70, device=dev)
-        dnd = synth.normal_bf16((1, Hd, Id), 0.02, seed=71, device=dev)
-        qgud, qdnd = q.qarl_quantize_weights(gud), q.qarl_quantize_weights(dnd)
-        del gud, dnd
-        xd = synth.normal_bf16((Td, Hd), 1.0, seed=72, device=dev)
-        offd = torch.tensor([0, Td], dtype=torch.int32, device=dev)
-        ad = torch.empty((Td, Id), dtype=torch.bfloat16, device=dev)
-        yd = torch.empty((Td, Hd), dtype=torch.bfloat16, device=dev)
-        wsd = torch.empty((max(q.qarl_qgemm_workspace_bytes(qgud, Td, Td, q.QARL_EPI_SILU_MUL),
-                               q.qarl_qgemm_workspace_bytes(qdnd, Td, Td, q.QARL_EPI_NONE), 16),), dtype=torch.uint8, device=dev)
-        ms_gud = timed(lambda: q.qarl_qgemm_grouped(qgud, xd, offd, Td, epilogue=q.QARL_EPI_SILU_MUL, out=ad,
-                                                    path=q.QARL_PATH_PREFILL, ws=wsd), 10, 2)
-        ms_dnd = timed(lambda: q.qarl_qgemm_grouped(qdnd, ad, offd, Td, out=yd, path=q.QARL_PATH_PREFILL, ws=wsd), 10, 2)
-        fl_d = 2 * Td * (2 * Id * Hd + Hd * Id)
-        extra["dense_mlp_w4a16_4096x12288_4096tok"] = {
-            "gate_up_ms": round(ms_gud, 4), "down_ms": round(ms_dnd, 4),
-            "TFLOP/s": round(fl_d / (ms_gud + ms_dnd) / 1e9, 1),
-            "frac_mfma_bf16": round(fl_d / (ms_gud + ms_dnd) / 1e9 / MFMA_BF16_PEAK_TF, 4)}
-        del qgud, qdnd, xd, ad, yd, wsd
+        if on("dense"):
+            # a dense SiLU-gated MLP of a second model shape (hidden 4096, intermediate 12288) through the same calls
+            Hd, Id, Td = 4096, 12288, 4096
+            gud = synth.normal_bf16((1, 2 * Id, Hd), 0.02, seed=70, device=dev)
+            dnd = synth.normal_bf16((1, Hd, Id), 0.02, seed=71, device=dev)
+            qgud, qdnd = q.qarl_quantize_weights(gud), q.qarl_quantize_weights(dnd)
+            del gud, dnd
+            xd = synth.normal_bf16((Td, Hd), 1.0, seed=72, device=dev)
+            offd = torch.tensor([0, Td], dtype=torch.int32, device=dev)
+            ad = torch.empty((Td, Id), dtype=torch.bfloat16, device=dev)
+            yd = torch.empty((Td, Hd), dtype=torch.bfloat16, device=dev)
+            wsd = torch.empty((max(q.qarl_qgemm_workspace_bytes(qgud, Td, Td, q.QARL_EPI_SILU_MUL),
+                                   q.qarl_qgemm_workspace_bytes(qdnd, Td, Td, q.QARL_EPI_NONE), 16),), dtype=torch.uint8, device=dev)
+            ms_gud = timed(lambda: q.qarl_qgemm_grouped(qgud, xd, offd, Td, epilogue=q.QARL_EPI_SILU_MUL, out=ad,
+                                                        path=q.QARL_PATH_PREFILL, ws=wsd), 10, 2)
+            ms_dnd = timed(lambda: q.qarl_qgemm_grouped(qdnd, ad, offd, Td, out=yd, path=q.QARL_PATH_PREFILL, ws=wsd), 10, 2)
+            fl_d = 2 * Td * (2 * Id * Hd + Hd * Id)
+            extra["dense_mlp_w4a16_4096x12288_4096tok"] = {
+                "gate_up_ms": round(ms_gud, 4), "down_ms": round(ms_dnd, 4),
+                "TFLOP/s": round(fl_d / (ms_gud + ms_dnd) / 1e9, 1),
+                "frac_mfma_bf16": round(fl_d / (ms_gud + ms_dnd) / 1e9 / MFMA_BF16_PEAK_TF, 4)}
+            del qgud, qdnd, xd, ad, yd, wsd
 
-        # FP8 W8A8 layer at 256 and 8192 tokens: the whole layer, and the two grouped GEMM launches on their own
-        qgu8 = outf
-        for T8, path, tag in ((256, q.QARL_PATH_DECODE, "decode"), (8192, q.QARL_PATH_PREFILL, "prefill")):
-            x8 = synth.normal_bf16((T8, H), 1.0, seed=50, device=dev)
-            lg8 = synth.router_logits(T8, E, seed=51, device=dev)
-            l8 = q.MoELayer(qgu8, qdn8, T8, TOPK, path, dev)
-            ms8 = timed(lambda: l8.forward(x8, lg8), 20, 3)
-            r8, M8 = l8.routing, T8 * TOPK
-            ms8_gu = timed(lambda: q.qarl_qgemm_grouped(qgu8, l8.xq, r8.offsets, M8, row_map=r8.tokens, x_scales=l8.sx,
-                                                        epilogue=q.QARL_EPI_SILU_MUL, out=l8.a, path=path), 20, 3)
-            y8 = torch.empty((M8, H), dtype=torch.float32, device=dev)
-            ms8_dn = timed(lambda: q.qarl_qgemm_grouped(qdn8, l8.aq, r8.offsets, M8, x_scales=l8.sa, out=y8,
-                                                        out_dtype=q.QARL_OUT_F32, path=path), 20, 3)
-            del y8
-            b8 = weight_bytes_fp8(E, 2 * I, H) + weight_bytes_fp8(E, H, I)
-            f8 = synth.flops_moe(T8)
-            extra["fp8_%s_%dtok" % (tag, T8)] = {
-                "layer_ms": round(ms8, 4), "gate_up_ms": round(ms8_gu, 4), "down_ms": round(ms8_dn, 4),
-                "weight_GB/s": round(b8 / ms8 / 1e6, 1), "frac_hbm": round(b8 / ms8 / 1e6 / HBM_PEAK_GBS, 4),
-                "gemm_weight_GB/s": round(b8 / (ms8_gu + ms8_dn) / 1e6, 1),
-                "gemm_frac_hbm": round(b8 / (ms8_gu + ms8_dn) / 1e6 / HBM_PEAK_GBS, 4),
-                "TFLOP/s": round(f8 / ms8 / 1e9, 1), "frac_mfma_fp8": round(f8 / ms8 / 1e9 / MFMA_FP8_PEAK_TF, 4),
-                "gemm_TFLOP/s": round(f8 / (ms8_gu + ms8_dn) / 1e9, 1),
-                "gemm_frac_mfma_fp8": round(f8 / (ms8_gu + ms8_dn) / 1e9 / MFMA_FP8_PEAK_TF, 4)}
-            del l8
-        del qgu8, qdn8, outf, outq
+        if on("fp8"):
+            # FP8 W8A8 layer at 256 and 8192 tokens: the whole layer, and the two grouped GEMM launches on their own
+            qgu8 = outf
+            for T8, path, tag in ((256, q.QARL_PATH_DECODE, "decode"), (8192, q.QARL_PATH_PREFILL, "prefill")):
+                x8 = synth.normal_bf16((T8, H), 1.0, seed=50, device=dev)
+                lg8 = synth.router_logits(T8, E, seed=51, device=dev)
+                l8 = q.MoELayer(qgu8, qdn8, T8, TOPK, path, dev)
+                ms8 = timed(lambda: l8.forward(x8, lg8), 20, 3)
+                r8, M8 = l8.routing, T8 * TOPK
+                ms8_gu = timed(lambda: q.qarl_qgemm_grouped(qgu8, l8.xq, r8.offsets, M8, row_map=r8.tokens, x_scales=l8.sx,
+                                                            epilogue=q.QARL_EPI_SILU_MUL, out=l8.a, path=path), 20, 3)
+                y8 = torch.empty((M8, H), dtype=torch.float32, device=dev)
+                ms8_dn = timed(lambda: q.qarl_qgemm_grouped(qdn8, l8.aq, r8.offsets, M8, x_scales=l8.sa, out=y8,
+                                                            out_dtype=q.QARL_OUT_F32, path=path), 20, 3)
+                del y8
+                b8 = weight_bytes_fp8(E, 2 * I, H) + weight_bytes_fp8(E, H, I)
+                f8 = synth.flops_moe(T8)
+                extra["fp8_%s_%dtok" % (tag, T8)] = {
+                    "layer_ms": round(ms8, 4), "gate_up_ms": round(ms8_gu, 4), "down_ms": round(ms8_dn, 4),
+                    "weight_GB/s": round(b8 / ms8 / 1e6, 1), "frac_hbm": round(b8 / ms8 / 1e6 / HBM_PEAK_GBS, 4),
+                    "gemm_weight_GB/s": round(b8 / (ms8_gu + ms8_dn) / 1e6, 1),
+                    "gemm_frac_hbm": round(b8 / (ms8_gu + ms8_dn) / 1e6 / HBM_PEAK_GBS, 4),
+                    "TFLOP/s": round(f8 / ms8 / 1e9, 1), "frac_mfma_fp8": round(f8 / ms8 / 1e9 / MFMA_FP8_PEAK_TF, 4),
+                    "gemm_TFLOP/s": round(f8 / (ms8_gu + ms8_dn) / 1e9, 1),
+                    "gemm_frac_mfma_fp8": round(f8 / (ms8_gu + ms8_dn) / 1e9 / MFMA_FP8_PEAK_TF, 4)}
+                del l8
+        del qdn8, outf, outq
 
-        # 48-layer stack: re-quantize every layer after a simulated update, then decode at 512 tokens
-        L = args.sweep_layers
-        if L > 0:
-            T5 = 512
-            masters, quant = [], []
-            for l in range(L):
-                gu, dn = synth.expert_weights(E, H, I, seed=7000 + 2 * l, device=dev)
-                masters.append((gu, dn))
-                quant.append((q.QWeight.empty(q.QARL_W4A16_G128, E, 2 * I, H, dev),
-                              q.QWeight.empty(q.QARL_W4A16_G128, E, H, I, dev)))
-            for l in range(L):   # the simulated update: w += N(0, 1e-4), rounded to bf16
-                masters[l] = (synth.perturb(masters[l][0], 1e-4, 8000 + l), synth.perturb(masters[l][1], 1e-4, 9000 + l))
-
-            def requant():
+        if on("stack"):
+            # 48-layer stack: re-quantize every layer after a simulated update, then decode at 512 tokens
+            L = args.sweep_layers
+            if L > 0:
+                T5 = 512
+                masters, quant = [], []
                 for l in range(L):
-                    q.qarl_quantize_weights(masters[l][0], out=quant[l][0])
-                    q.qarl_quantize_weights(masters[l][1], out=quant[l][1])
-            ms_rq = timed(requant, 3, 1)
-            rq_bytes = L * (E * 3 * I * H * 2 + weight_bytes_w4a16(E, 2 * I, H) + weight_bytes_w4a16(E, H, I))
-            del masters
-            lay5 = [q.MoELayer(quant[l][0], quant[l][1], T5, TOPK, q.QARL_PATH_DECODE, dev) for l in range(L)]
-            x5 = [synth.normal_bf16((T5, H), 1.0, seed=60 + l, device=dev) for l in range(4)]
-            lg5 = [synth.router_logits(T5, E, seed=70 + l, device=dev) for l in range(4)]
+                    gu, dn = synth.expert_weights(E, H, I, seed=7000 + 2 * l, device=dev)
+                    masters.append((gu, dn))
+                    quant.append((q.QWeight.empty(q.QARL_W4A16_G128, E, 2 * I, H, dev),
+                                  q.QWeight.empty(q.QARL_W4A16_G128, E, H, I, dev)))
+                for l in range(L):   # the simulated update: w += N(0, 1e-4), rounded to bf16
+                    masters[l] = (synth.perturb(masters[l][0], 1e-4, 8000 + l), synth.perturb(masters[l][1], 1e-4, 9000 + l))
 
-            def sweep():
-                for l in range(L):
-                    lay5[l].forward(x5[l % 4], lg5[l % 4])
-            ms_sw = timed(sweep, 5, 1)
-            sw_bytes = L * (weight_bytes_w4a16(E, 2 * I, H) + weight_bytes_w4a16(E, H, I))
-            extra["stack_requantize_%dlayers" % L] = {"ms": round(ms_rq, 3), "GB/s": round(rq_bytes / ms_rq / 1e6, 1),
-                                                      "frac_hbm": round(rq_bytes / ms_rq / 1e6 / HBM_PEAK_GBS, 4)}
-            extra["stack_decode_sweep_%dlayers_512tok" % L] = {
-                "ms": round(ms_sw, 3), "weight_GB/s": round(sw_bytes / ms_sw / 1e6, 1),
-                "frac_hbm": round(sw_bytes / ms_sw / 1e6 / HBM_PEAK_GBS, 4),
-                "TFLOP/s": round(L * synth.flops_moe(T5) / ms_sw / 1e9, 1)}
+                def requant():
+                    for l in range(L):
+                        q.qarl_quantize_weights(masters[l][0], out=quant[l][0])
+                        q.qarl_quantize_weights(masters[l][1], out=quant[l][1])
+                ms_rq = timed(requant, 3, 1)
+                rq_bytes = L * (E * 3 * I * H * 2 + weight_bytes_w4a16(E, 2 * I, H) + weight_bytes_w4a16(E, H, I))
+                del masters
+                lay5 = [q.MoELayer(quant[l][0], quant[l][1], T5, TOPK, q.QARL_PATH_DECODE, dev) for l in range(L)]
+                x5 = [synth.normal_bf16((T5, H), 1.0, seed=60 + l, device=dev) for l in range(4)]
+                lg5 = [synth.router_logits(T5, E, seed=70 + l, device=dev) for l in range(4)]
+
+                def sweep():
+                    for l in range(L):
+                        lay5[l].forward(x5[l % 4], lg5[l % 4])
+                ms_sw = timed(sweep, 5, 1)
+
+                # the two GEMM calls of the sweep on their own (ids of the last pass; down includes its combine launch)
+                def sweep_gu():
+                    for l in range(L):
+                        ly = lay5[l]
+                        q.qarl_qgemm_routed(ly.gu, x5[l % 4], ly.routing.ids, T5, TOPK, True,
+                                            epilogue=q.QARL_EPI_SILU_MUL, out=ly.a, ws=ly.ws)
+
+                def sweep_dn():
+                    for l in range(L):
+                        ly = lay5[l]
+                        q.qarl_qgemm_routed(ly.dn, ly.a, ly.routing.ids, T5, TOPK, False, epilogue=q.QARL_EPI_COMBINE,
+                                            combine_w=ly.routing.w, out=ly.out, ws=ly.ws)
+                ms_sw_gu = timed(sweep_gu, 5, 1) / L
+                ms_sw_dn = timed(sweep_dn, 5, 1) / L
+                sw_bytes = L * (weight_bytes_w4a16(E, 2 * I, H) + weight_bytes_w4a16(E, H, I))
+                extra["stack_requantize_%dlayers" % L] = {"ms": round(ms_rq, 3), "GB/s": round(rq_bytes / ms_rq / 1e6, 1),
+                                                          "frac_hbm": round(rq_bytes / ms_rq / 1e6 / HBM_PEAK_GBS, 4)}
+                extra["stack_decode_sweep_%dlayers_512tok" % L] = {
+                    "ms": round(ms_sw, 3), "weight_GB/s": round(sw_bytes / ms_sw / 1e6, 1),
+                    "frac_hbm": round(sw_bytes / ms_sw / 1e6 / HBM_PEAK_GBS, 4),
+                    "TFLOP/s": round(L * synth.flops_moe(T5) / ms_sw / 1e9, 1),
+                    "ms_per_layer": round(ms_sw / L, 5), "gate_up_ms_per_layer": round(ms_sw_gu, 5),
+                    "down_combine_ms_per_layer": round(ms_sw_dn, 5)}
         result["extra"] = extra
 
     print(json.dumps(result))

@@ -85,8 +85,11 @@ size_t lds_bytes(int K, int MT)
     return rows * 8 + 16 + G * rows * 4 + (size_t)kWaves * 2 * 32 * G * 2 + rows * x_stride(K);
 }
 
-// EPI: NONE or SILU_MUL; MT: 32-row token tiles per block; R: ring depth in scale groups (divides K/128).
-template <int EPI, int MT, int R>
+// EPI: NONE or SILU_MUL; MT: 32-row token tiles per block; R: ring depth in scale groups (divides K/128);
+// NT: the weight stream uses nontemporal loads (every line is read once).  With several row blocks per (expert,
+// slice) the same lines are read by neighbouring workgroups of one XCD: there the loads stay temporal, so that the
+// second reader finds them in that XCD's L2.
+template <int EPI, int MT, int R, bool NT>
 __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_kernel(W4Params p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -143,7 +146,10 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_kernel(W4Params p
     Slot ring[R];
     auto fill = [&](Slot &dst, int r, const uint32_t *src) {
 #pragma unroll
-        for (int L = 0; L < 2; ++L) dst.w[L] = __builtin_nontemporal_load((const u32x4 *)(src + r * 256 + L * 128));
+        for (int L = 0; L < 2; ++L) {
+            const u32x4 *a = (const u32x4 *)(src + r * 256 + L * 128);
+            dst.w[L] = NT ? __builtin_nontemporal_load(a) : *a;
+        }
     };
     auto fill_ring = [&](int pi, int g0) {
         const uint32_t *src = batch_src(pi, g0);
@@ -433,8 +439,8 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_kernel(W4Params p
     }
 }
 
-template <int EPI, int MT, int R>
-int launch_cfg(const W4Params &p, hipStream_t s)
+template <int EPI, int MT, int R, bool NT>
+int launch_cfg_nt(const W4Params &p, hipStream_t s)
 {
     size_t lds = lds_bytes(p.K, MT);
     if (p.ids) lds += 8 * (size_t)kIdsRows + 4 * kWaves;
@@ -444,12 +450,18 @@ int launch_cfg(const W4Params &p, hipStream_t s)
         return QARL_ERR_UNSUPPORTED;
     }
     static LdsLimitOnce once;
-    auto kern = qgemm_stream_w4_kernel<EPI, MT, R>;
+    auto kern = qgemm_stream_w4_kernel<EPI, MT, R, NT>;
     if (int rc = raise_lds_limit((const void *)kern, once, "hipFuncSetAttribute(stream w4)")) return rc;
     const int64_t units = (int64_t)p.E << p.slice_sh;
     const int64_t grid = (((units + 7) / 8) * 8) << p.msplit_sh;
     kern<<<dim3((unsigned)grid), dim3(kThreads), lds, s>>>(p);
     return check_hip(hipGetLastError(), "qgemm_stream_w4_kernel");
+}
+
+template <int EPI, int MT, int R>
+int launch_cfg(const W4Params &p, hipStream_t s)
+{
+    return p.msplit_sh == 0 ? launch_cfg_nt<EPI, MT, R, true>(p, s) : launch_cfg_nt<EPI, MT, R, false>(p, s);
 }
 
 template <int EPI, int MT>
