@@ -24,6 +24,10 @@ def lib():
         _lib.oracle_e4m3_encode.argtypes = [C.c_double]
         _lib.oracle_e4m3_encode_fast.restype = C.c_uint8
         _lib.oracle_e4m3_encode_fast.argtypes = [C.c_double]
+        _lib.oracle_e2m1_decode.restype = C.c_double
+        _lib.oracle_e2m1_decode.argtypes = [C.c_uint8]
+        _lib.oracle_e2m1_encode.restype = C.c_uint8
+        _lib.oracle_e2m1_encode.argtypes = [C.c_double]
         _lib.oracle_bf16_from_double.restype = C.c_uint16
         _lib.oracle_bf16_from_double.argtypes = [C.c_double]
         _lib.oracle_bf16_to_double.restype = C.c_double
@@ -68,6 +72,30 @@ def e4m3_encode(x, fast=False):
     x = np.asarray(x, dtype=np.float64)
     f = lib().oracle_e4m3_encode_fast if fast else lib().oracle_e4m3_encode
     return np.array([f(float(v)) for v in x.ravel()], dtype=np.uint8).reshape(x.shape)
+
+
+def e2m1_decode(codes):
+    codes = _c(codes, np.uint8)
+    f = lib().oracle_e2m1_decode
+    tab = np.array([f(c) for c in range(16)], dtype=np.float64)
+    return tab[codes & 15]
+
+
+def e2m1_encode(x):
+    x = np.asarray(x, dtype=np.float64)
+    f = lib().oracle_e2m1_encode
+    return np.array([f(float(v)) for v in x.ravel()], dtype=np.uint8).reshape(x.shape)
+
+
+def quantize_fp4_rows(x_bits):
+    """x_bits uint16 [..., K] -> e2m1 codes uint8 [..., K] (one per byte, 0..15), scales float32 [...]."""
+    x = _c(x_bits, np.uint16)
+    K = x.shape[-1]
+    rows = x.size // K
+    codes = np.empty(x.shape, dtype=np.uint8)
+    scales = np.empty(x.shape[:-1], dtype=np.float32)
+    lib().oracle_quantize_fp4_rows(_p(x), C.c_int64(rows), C.c_int(K), _p(codes), _p(scales))
+    return codes, scales
 
 
 def quantize_int4(w_bits, group=128):
@@ -161,6 +189,39 @@ def qgemm_fp8(xq, sx, wq, sw, offsets, row_map=None):
     out = np.zeros((M, N), dtype=np.float64)
     lib().oracle_qgemm_fp8(_p(xq), _p(sx), C.c_int(K), _p(rm), C.c_int64(M), _p(offsets), C.c_int(E),
                            _p(wq), _p(sw), C.c_int(N), _p(out))
+    return out
+
+
+def qgemm_fp4w(xq, sx, wq, sw, offsets, row_map=None):
+    """e4m3 activations x e2m1 weights (codes one per byte); returns float64 [M, N]."""
+    xq = _c(xq, np.uint8)
+    sx = _c(sx, np.float32)
+    wq = _c(wq, np.uint8)
+    sw = _c(sw, np.float32)
+    offsets = _c(offsets, np.int32)
+    E, N, K = wq.shape
+    M = int(offsets[-1])
+    rm = None if row_map is None else _c(row_map, np.int32)
+    out = np.zeros((M, N), dtype=np.float64)
+    lib().oracle_qgemm_fp4w(_p(xq), _p(sx), C.c_int(K), _p(rm), C.c_int64(M), _p(offsets), C.c_int(E),
+                            _p(wq), _p(sw), C.c_int(N), _p(out))
+    return out
+
+
+def qgemm_w4a8(xq, sx, codes, scales, offsets, row_map=None, group=128):
+    """e4m3 activations x int4 g128 weights; returns float64 [M, N]."""
+    xq = _c(xq, np.uint8)
+    sx = _c(sx, np.float32)
+    codes = _c(codes, np.uint32)
+    scales = _c(scales, np.uint16)
+    offsets = _c(offsets, np.int32)
+    E, N, K8 = codes.shape
+    K = K8 * 8
+    M = int(offsets[-1])
+    rm = None if row_map is None else _c(row_map, np.int32)
+    out = np.zeros((M, N), dtype=np.float64)
+    lib().oracle_qgemm_w4a8(_p(xq), _p(sx), C.c_int(K), _p(rm), C.c_int64(M), _p(offsets), C.c_int(E),
+                            _p(codes), _p(scales), C.c_int(N), C.c_int(group), _p(out))
     return out
 
 

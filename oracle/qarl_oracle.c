@@ -204,6 +204,54 @@ void oracle_quantize_fp8_rows(const uint16_t *x, int64_t rows, int K, uint8_t *c
     }
 }
 
+/* -------------------------------------------------------------- e2m1 (FP4) -- */
+/* Section 2.2, FP Quant with alpha = 6 for FP4: the e2m1 format (1 sign, 2 exponent, 1 mantissa bit, bias 1,
+ * no infinities or NaN).  Code c = s e1 e0 m; magnitudes 0, 0.5 (the one subnormal), 1, 1.5, 2, 3, 4, 6. */
+double oracle_e2m1_decode(uint8_t c)
+{
+    int s = (c >> 3) & 1, e = (c >> 1) & 3, m = c & 1;
+    double v = (e == 0) ? 0.5 * m : ldexp(1.0 + 0.5 * m, e - 1);
+    return s ? -v : v;
+}
+
+/* Nearest representable value, ties to the even code, saturating at +-6. */
+uint8_t oracle_e2m1_encode(double x)
+{
+    if (isnan(x)) return 0;
+    uint8_t sign = signbit(x) ? 8 : 0;
+    double a = fabs(x);
+    if (a >= 6.0) return sign | 7;
+    int lo = 0;                                      /* largest magnitude code with value <= a */
+    for (int c = 0; c <= 7; ++c)
+        if (oracle_e2m1_decode((uint8_t)c) <= a) lo = c;
+    double dl = a - oracle_e2m1_decode((uint8_t)lo);
+    double dh = oracle_e2m1_decode((uint8_t)(lo + 1)) - a;
+    int pick = (dl < dh) ? lo : (dl > dh) ? lo + 1 : ((lo & 1) ? lo + 1 : lo);
+    return sign | (uint8_t)pick;
+}
+
+/* FP Quant of section 2.2 with alpha = 6: s = max|row| / 6 (fp32 divide), code = e2m1(w / s) with an fp32
+ * divide, one scale per row (output channel).  Codes are returned one per byte (values 0..15); how a
+ * consumer packs them is not part of the definition.  A zero row has scale 0 and codes +0. */
+void oracle_quantize_fp4_rows(const uint16_t *x, int64_t rows, int K, uint8_t *codes, float *scales)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        float am = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            float a = fabsf(bf16_to_f32(x[r * K + k]));
+            if (a > am) am = a;
+        }
+        volatile float s = am / 6.0f;
+        scales[r] = s;
+        for (int k = 0; k < K; ++k) {
+            if (s == 0.0f) { codes[r * K + k] = 0; continue; }
+            volatile float t = bf16_to_f32(x[r * K + k]) / s;
+            codes[r * K + k] = oracle_e2m1_encode((double)t);
+        }
+    }
+}
+
 /* ------------------------------------------------------------------ router -- */
 /* Softmax over all E logits, the top `topk` experts ordered by (logit
  * descending, expert id ascending), their probabilities renormalised to 1. */
@@ -310,6 +358,61 @@ void oracle_qgemm_fp8(const uint8_t *xq, const float *sx, int K, const int32_t *
                 out[i * N + n] = (double)sx[r] * (double)sw[(int64_t)e * N + n] * a;
             }
     }
+    (void)M;
+}
+
+/* eq. (2) with FP4 weights: Y[i][n] = s_x[row] * s_w[e][n] * sum_k x_q[row][k] * w_q[e][n][k], x_q e4m3 codes,
+ * w_q e2m1 codes (one per byte). */
+void oracle_qgemm_fp4w(const uint8_t *xq, const float *sx, int K, const int32_t *row_map,
+                       int64_t M, const int32_t *offsets, int E, const uint8_t *wq,
+                       const float *sw, int N, double *out)
+{
+    double dec8[256], dec4[16];
+    for (int c = 0; c < 256; ++c) dec8[c] = oracle_e4m3_decode((uint8_t)c);
+    for (int c = 0; c < 16; ++c) dec4[c] = oracle_e2m1_decode((uint8_t)c);
+    for (int e = 0; e < E; ++e) {
+        int64_t lo = offsets[e], hi = offsets[e + 1];
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t i = lo; i < hi; ++i)
+            for (int n = 0; n < N; ++n) {
+                int64_t r = row_map ? (int64_t)row_map[i] : i;
+                const uint8_t *xr = xq + r * K;
+                const uint8_t *wn = wq + ((int64_t)e * N + n) * K;
+                double a = 0.0;
+                for (int k = 0; k < K; ++k) a += dec8[xr[k]] * dec4[wn[k] & 15];
+                out[i * N + n] = (double)sx[r] * (double)sw[(int64_t)e * N + n] * a;
+            }
+    }
+    (void)M;
+}
+
+/* W4A8: the integer weight quantizer of eq. (1) (int4, one bf16 scale per group of k) with the activations of
+ * eq. (2) (e4m3 codes, one fp32 scale per token row):
+ * Y[i][n] = s_x[row] * sum_k (s_w[e][n][k / group] * q[e][n][k]) * x_q[row][k]. */
+void oracle_qgemm_w4a8(const uint8_t *xq, const float *sx, int K, const int32_t *row_map, int64_t M,
+                       const int32_t *offsets, int E, const uint32_t *codes, const uint16_t *scales,
+                       int N, int group, double *out)
+{
+    double dec8[256];
+    for (int c = 0; c < 256; ++c) dec8[c] = oracle_e4m3_decode((uint8_t)c);
+    float *wd = (float *)malloc(sizeof(float) * (size_t)N * K);
+    for (int e = 0; e < E; ++e) {
+        int64_t lo = offsets[e], hi = offsets[e + 1];
+        if (hi <= lo) continue;
+        oracle_dequant_int4(codes + (int64_t)e * N * (K / 8),
+                            scales + (int64_t)e * N * (K / group), N, K, group, wd);
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t i = lo; i < hi; ++i)
+            for (int n = 0; n < N; ++n) {
+                int64_t r = row_map ? (int64_t)row_map[i] : i;
+                const uint8_t *xr = xq + r * K;
+                const float *wn = wd + (int64_t)n * K;
+                double a = 0.0;
+                for (int k = 0; k < K; ++k) a += (double)wn[k] * dec8[xr[k]];
+                out[i * N + n] = (double)sx[r] * a;
+            }
+    }
+    free(wd);
     (void)M;
 }
 
