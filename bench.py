@@ -41,6 +41,10 @@ def weight_bytes_fp8(E, N, K):
     return E * N * (K + 4)
 
 
+def weight_bytes_fp4(E, N, K):
+    return E * N * (K // 2 + 4)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -231,6 +235,17 @@ def main():
         extra["quantize_fp8_gate_up"] = {"ms": round(ms, 4), "GB/s": round(qb8 / ms / 1e6, 1),
                                          "frac_hbm": round(qb8 / ms / 1e6 / HBM_PEAK_GBS, 4), "bytes": qb8}
         qdn8 = q.qarl_quantize_weights(dn, q.QARL_FP8_E4M3_CH)
+        lowbit = [("fp8", outf, qdn8, weight_bytes_fp8(E, 2 * I, H) + weight_bytes_fp8(E, H, I))]
+        if on("fp8"):   # the two 4-bit-weight x e4m3-activation formats ride along in the fp8 rows
+            outf4 = q.QWeight.empty(q.QARL_FP4_E2M1_CH, E, 2 * I, H, dev)
+            ms = timed(lambda: q.qarl_quantize_weights(gu, q.QARL_FP4_E2M1_CH, out=outf4), 20, 3)
+            qb4 = gu.numel() * 2 + weight_bytes_fp4(E, 2 * I, H)
+            extra["quantize_fp4_gate_up"] = {"ms": round(ms, 4), "GB/s": round(qb4 / ms / 1e6, 1),
+                                             "frac_hbm": round(qb4 / ms / 1e6 / HBM_PEAK_GBS, 4), "bytes": qb4}
+            lowbit.append(("fp4", outf4, q.qarl_quantize_weights(dn, q.QARL_FP4_E2M1_CH),
+                           weight_bytes_fp4(E, 2 * I, H) + weight_bytes_fp4(E, H, I)))
+            lowbit.append(("w4a8", q.qarl_quantize_weights(gu, q.QARL_W4A8_G128), q.qarl_quantize_weights(dn, q.QARL_W4A8_G128),
+                           weight_bytes_w4a16(E, 2 * I, H) + weight_bytes_w4a16(E, H, I)))
         del gu, dn
 
         if on("prefill"):
@@ -315,22 +330,23 @@ def main():
 
         if on("fp8"):
             # FP8 W8A8 layer at 256 and 8192 tokens: the whole layer, and the two grouped GEMM launches on their own
-            qgu8 = outf
-            for T8, path, tag in ((256, q.QARL_PATH_DECODE, "decode"), (8192, q.QARL_PATH_PREFILL, "prefill")):
+            for (fname, qgu8, qdn8, b8), (T8, path, tag) in [(f, c) for f in lowbit for c in
+                                                             ((256, q.QARL_PATH_DECODE, "decode"),
+                                                              (8192, q.QARL_PATH_PREFILL, "prefill"))]:
                 x8 = synth.normal_bf16((T8, H), 1.0, seed=50, device=dev)
                 lg8 = synth.router_logits(T8, E, seed=51, device=dev)
                 l8 = q.MoELayer(qgu8, qdn8, T8, TOPK, path, dev)
                 ms8 = timed(lambda: l8.forward(x8, lg8), 20, 3)
                 r8, M8 = l8.routing, T8 * TOPK
                 ms8_gu = timed(lambda: q.qarl_qgemm_grouped(qgu8, l8.xq, r8.offsets, M8, row_map=r8.tokens, x_scales=l8.sx,
-                                                            epilogue=q.QARL_EPI_SILU_MUL, out=l8.a, path=path), 20, 3)
+                                                            epilogue=q.QARL_EPI_SILU_MUL, out=l8.a, path=path,
+                                                            ws=l8.ws), 20, 3)
                 y8 = torch.empty((M8, H), dtype=torch.float32, device=dev)
                 ms8_dn = timed(lambda: q.qarl_qgemm_grouped(qdn8, l8.aq, r8.offsets, M8, x_scales=l8.sa, out=y8,
-                                                            out_dtype=q.QARL_OUT_F32, path=path), 20, 3)
+                                                            out_dtype=q.QARL_OUT_F32, path=path, ws=l8.ws), 20, 3)
                 del y8
-                b8 = weight_bytes_fp8(E, 2 * I, H) + weight_bytes_fp8(E, H, I)
                 f8 = synth.flops_moe(T8)
-                extra["fp8_%s_%dtok" % (tag, T8)] = {
+                extra["%s_%s_%dtok" % (fname, tag, T8)] = {
                     "layer_ms": round(ms8, 4), "gate_up_ms": round(ms8_gu, 4), "down_ms": round(ms8_dn, 4),
                     "weight_GB/s": round(b8 / ms8 / 1e6, 1), "frac_hbm": round(b8 / ms8 / 1e6 / HBM_PEAK_GBS, 4),
                     "gemm_weight_GB/s": round(b8 / (ms8_gu + ms8_dn) / 1e6, 1),
@@ -339,7 +355,7 @@ def main():
                     "gemm_TFLOP/s": round(f8 / (ms8_gu + ms8_dn) / 1e9, 1),
                     "gemm_frac_mfma_fp8": round(f8 / (ms8_gu + ms8_dn) / 1e9 / MFMA_FP8_PEAK_TF, 4)}
                 del l8
-        del qdn8, outf, outq
+        del lowbit, qdn8, outf, outq
 
         if on("stack"):
             # 48-layer stack: re-quantize every layer after a simulated update, then decode at 512 tokens

@@ -39,9 +39,13 @@ typedef enum {
 
 /* Weight formats (the WxAy schemes of section 2.2). */
 typedef enum {
-    QARL_W4A16_G128 = 1, /* int4 symmetric, one bf16 scale per 128 consecutive k; bf16 activations */
-    QARL_FP8_E4M3_CH = 2 /* e4m3 weights, one fp32 scale per output channel; e4m3 activations, one
-                            fp32 scale per token row */
+    QARL_W4A16_G128 = 1,  /* int4 symmetric, one bf16 scale per 128 consecutive k; bf16 activations */
+    QARL_FP8_E4M3_CH = 2, /* e4m3 weights, one fp32 scale per output channel; e4m3 activations, one
+                             fp32 scale per token row */
+    QARL_FP4_E2M1_CH = 3, /* FP4 weights: e2m1 (the FP quantizer's alpha = 6), one fp32 scale per output
+                             channel; activations as for FP8_E4M3_CH (a floating-point W4A8) */
+    QARL_W4A8_G128 = 4    /* the weights of W4A16_G128 (same codes, scales and quantizer) with the
+                             activations of FP8_E4M3_CH: the W4A8 scheme of the scheme ablation */
 } qarl_format;
 
 /* Which kernel family runs the contraction.  Both read the same codes and scales and
@@ -70,6 +74,10 @@ typedef enum { QARL_OUT_BF16 = 0, QARL_OUT_F32 = 1 } qarl_out_dtype;
  *               scales bf16   [E][N][K/128]; dequantized weight = float(scale) * q, exact in
  *                      fp32 and never rounded to 16 bits.
  *   FP8_E4M3_CH: codes uint8  [E][N][K] (e4m3 bit patterns); scales float [E][N].
+ *   FP4_E2M1_CH: codes uint32 [E][N][K/8]: a word holds 8 consecutive k as e2m1 codes (sign, 2 exponent bits,
+ *                      1 mantissa bit; magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6): byte b of the word carries
+ *                      element b in its low nibble and element 4 + b in its high nibble; scales float [E][N].
+ *   W4A8_G128:   as W4A16_G128.
  * Requirements: K % 128 == 0, N % 32 == 0, buffers 16-byte aligned. */
 typedef struct {
     int32_t fmt; /* qarl_format */
@@ -95,6 +103,9 @@ size_t qarl_logprob_workspace_bytes(int T, int H, int V);
  *     dividing by the stored scale; a zero group gets scale 0 and codes 0.
  *   FP8_E4M3_CH (FP Quant, alpha = 448): per row, scale = absmax / 448 (fp32),
  *     code = e4m3_rne_saturating(w / scale); a zero row gets scale 0 and codes +0.
+ *   FP4_E2M1_CH (FP Quant, alpha = 6): per row, scale = absmax / 6 (fp32),
+ *     code = e2m1_rne_saturating(w / scale); a zero row gets scale 0 and codes +0.
+ *   W4A8_G128: as W4A16_G128.
  * Errors: INVALID_ARG (null pointers, E/N/K <= 0, wrong group), ALIGNMENT, UNSUPPORTED. */
 int qarl_quantize_weights(const void *w_bf16, const qarl_qweight *out, void *stream);
 
@@ -122,7 +133,8 @@ int qarl_moe_route(const void *logits_bf16, int T, int E, int topk, int renorm, 
  * [expert_offsets[e], expert_offsets[e+1]), multiplies expert e's matrix and reads
  * activation row row_map[i] (row i if row_map is NULL).  M = expert_offsets[E] must be
  * passed by the caller (host value).
- *   x          W4A16: bf16 [x_rows][K];  FP8: uint8 e4m3 [x_rows][K] with x_scales float [x_rows]
+ *   x          W4A16: bf16 [x_rows][K];  FP8, FP4 and W4A8: uint8 e4m3 [x_rows][K] with x_scales float [x_rows]
+ *              (W4A8: Y = s_x * X_q * (s_w q)^T, the integer weights of eq. (1) under the activations of eq. (2))
  *   epilogue   NONE:     out [M][N]
  *              SILU_MUL: rows [0,N/2) of each expert matrix are the gate, [N/2,N) the up
  *                        projection; out bf16 [M][N/2], rounded once from fp32

@@ -15,7 +15,9 @@ LIB_PATH = os.path.join(HERE, "libqarl.so")
 
 QARL_OK = 0
 QARL_ERR_INVALID_ARG, QARL_ERR_UNSUPPORTED, QARL_ERR_ALIGNMENT, QARL_ERR_WORKSPACE, QARL_ERR_HIP = -1, -2, -3, -4, -5
-QARL_W4A16_G128, QARL_FP8_E4M3_CH = 1, 2
+QARL_W4A16_G128, QARL_FP8_E4M3_CH, QARL_FP4_E2M1_CH, QARL_W4A8_G128 = 1, 2, 3, 4
+INT4_FORMATS = (QARL_W4A16_G128, QARL_W4A8_G128)          # int4 g128 codes + bf16 group scales
+E4M3_ACT_FORMATS = (QARL_FP8_E4M3_CH, QARL_FP4_E2M1_CH, QARL_W4A8_G128)   # e4m3 activations + row scales
 QARL_PATH_AUTO, QARL_PATH_DECODE, QARL_PATH_PREFILL = 0, 1, 2
 QARL_EPI_NONE, QARL_EPI_SILU_MUL, QARL_EPI_COMBINE = 0, 1, 2
 QARL_OUT_BF16, QARL_OUT_F32 = 0, 1
@@ -99,14 +101,17 @@ class QWeight:
     def __init__(self, fmt, E, N, K, codes, scales):
         self.fmt, self.E, self.N, self.K = fmt, E, N, K
         self.codes, self.scales = codes, scales
-        self.desc = qarl_qweight(fmt, E, N, K, 128 if fmt == QARL_W4A16_G128 else 0,
+        self.desc = qarl_qweight(fmt, E, N, K, 128 if fmt in INT4_FORMATS else 0,
                                  codes.data_ptr(), scales.data_ptr())
 
     @staticmethod
     def empty(fmt, E, N, K, device="cuda"):
-        if fmt == QARL_W4A16_G128:
+        if fmt in INT4_FORMATS:
             codes = torch.empty((E, N, K // 8), dtype=torch.int32, device=device)
             scales = torch.empty((E, N, K // 128), dtype=torch.bfloat16, device=device)
+        elif fmt == QARL_FP4_E2M1_CH:
+            codes = torch.empty((E, N, K // 8), dtype=torch.int32, device=device)
+            scales = torch.empty((E, N), dtype=torch.float32, device=device)
         else:
             codes = torch.empty((E, N, K), dtype=torch.uint8, device=device)
             scales = torch.empty((E, N), dtype=torch.float32, device=device)
@@ -269,10 +274,10 @@ class MoELayer:
 
     def __init__(self, gate_up: QWeight, down: QWeight, T, topk=8, path=QARL_PATH_AUTO, device="cuda", routed=None):
         self.gu, self.dn, self.T, self.topk, self.path = gate_up, down, T, topk, path
-        self.fp8 = gate_up.fmt == QARL_FP8_E4M3_CH
+        self.fp8 = gate_up.fmt in E4M3_ACT_FORMATS        # e4m3 activations with per-row scales
         # decode-sized W4A16 batches skip the grouping pass: the GEMMs read the router's ids themselves
         self.routed = (routed if routed is not None else
-                       (not self.fp8 and path == QARL_PATH_DECODE and 0 < T <= 512 and T * topk <= 4096))
+                       (gate_up.fmt == QARL_W4A16_G128 and path == QARL_PATH_DECODE and 0 < T <= 512 and T * topk <= 4096))
         E, I, H = gate_up.E, gate_up.N // 2, gate_up.K
         self.E, self.I, self.H = E, I, H
         M = T * topk
@@ -301,7 +306,7 @@ class MoELayer:
         if self.fp8:
             qarl_quantize_rows_fp8(x, self.xq, self.sx)
             qarl_qgemm_grouped(self.gu, self.xq, r.offsets, self.M, row_map=r.tokens, x_scales=self.sx,
-                               epilogue=QARL_EPI_SILU_MUL, out=self.a, path=self.path)
+                               epilogue=QARL_EPI_SILU_MUL, out=self.a, path=self.path, ws=self.ws)
             qarl_quantize_rows_fp8(self.a, self.aq, self.sa)
             qarl_qgemm_grouped(self.dn, self.aq, r.offsets, self.M, x_scales=self.sa, epilogue=QARL_EPI_COMBINE,
                                combine_w=r.w, sorted_pairs=r.pairs, T=self.T, topk=self.topk, out=self.out,

@@ -48,7 +48,7 @@ static int check_qweight(const qarl_qweight *w, const char *who)
         set_error("%s: null weight descriptor", who);
         return QARL_ERR_INVALID_ARG;
     }
-    if (w->fmt != QARL_W4A16_G128 && w->fmt != QARL_FP8_E4M3_CH) {
+    if (w->fmt != QARL_W4A16_G128 && w->fmt != QARL_FP8_E4M3_CH && w->fmt != QARL_FP4_E2M1_CH && w->fmt != QARL_W4A8_G128) {
         set_error("%s: unknown weight format %d", who, w->fmt);
         return QARL_ERR_UNSUPPORTED;
     }
@@ -60,8 +60,8 @@ static int check_qweight(const qarl_qweight *w, const char *who)
         set_error("%s: need K %% 128 == 0 and N %% 32 == 0 (got N=%d, K=%d)", who, w->N, w->K);
         return QARL_ERR_UNSUPPORTED;
     }
-    if (w->fmt == QARL_W4A16_G128 && w->group != 128) {
-        set_error("%s: W4A16 supports group 128 only (got %d)", who, w->group);
+    if ((w->fmt == QARL_W4A16_G128 || w->fmt == QARL_W4A8_G128) && w->group != 128) {
+        set_error("%s: int4 weights support group 128 only (got %d)", who, w->group);
         return QARL_ERR_UNSUPPORTED;
     }
     if (!w->codes || !w->scales) {
@@ -90,15 +90,30 @@ static size_t ws_stage_bytes(const qarl_qweight *W, int64_t M, int epilogue)
     return epilogue == QARL_EPI_COMBINE ? align256((size_t)M * (size_t)W->N * sizeof(float)) : 0;
 }
 
+static bool int4_weights(int fmt) { return fmt == QARL_W4A16_G128 || fmt == QARL_W4A8_G128; }
+static bool fp8_activations(int fmt) { return fmt == QARL_FP8_E4M3_CH || fmt == QARL_FP4_E2M1_CH || fmt == QARL_W4A8_G128; }
+
 static size_t ws_sums_bytes(const qarl_qweight *W, int64_t x_rows)
 {
-    return W->fmt == QARL_W4A16_G128 ? align256((size_t)x_rows * (size_t)(W->K / 128) * sizeof(float)) : 0;
+    return int4_weights(W->fmt) ? align256((size_t)x_rows * (size_t)(W->K / 128) * sizeof(float)) : 0;
+}
+
+// Format bridges: W4A8 widens the e4m3 activations to bf16 (exact) for the W4A16 kernels; the tiled path of FP4
+// widens the e2m1 weights to e4m3 bytes (exact) for the FP8 kernel.
+static size_t ws_xwide_bytes(const qarl_qweight *W, int64_t x_rows)
+{
+    return W->fmt == QARL_W4A8_G128 ? align256((size_t)x_rows * (size_t)W->K * 2) : 0;
+}
+
+static size_t ws_wwide_bytes(const qarl_qweight *W)
+{
+    return W->fmt == QARL_FP4_E2M1_CH ? align256((size_t)W->E * (size_t)W->N * (size_t)W->K) : 0;
 }
 
 size_t qarl_qgemm_workspace_bytes(const qarl_qweight *W, int64_t x_rows, int64_t M, int epilogue)
 {
     if (!W || M <= 0 || x_rows <= 0 || W->N <= 0 || W->K <= 0) return 0;
-    return ws_stage_bytes(W, M, epilogue) + ws_sums_bytes(W, x_rows);
+    return ws_stage_bytes(W, M, epilogue) + ws_sums_bytes(W, x_rows) + ws_xwide_bytes(W, x_rows) + ws_wwide_bytes(W);
 }
 
 size_t qarl_logprob_workspace_bytes(int T, int H, int V)
@@ -120,8 +135,10 @@ int qarl_quantize_weights(const void *w_bf16, const qarl_qweight *out, void *str
         return QARL_ERR_ALIGNMENT;
     }
     const int64_t rows = (int64_t)out->E * out->N;
-    if (out->fmt == QARL_W4A16_G128)
+    if (int4_weights(out->fmt))
         return launch_quantize_int4(w_bf16, rows, out->K, out->codes, out->scales, (hipStream_t)stream);
+    if (out->fmt == QARL_FP4_E2M1_CH)
+        return launch_quantize_fp4_rows(w_bf16, rows, out->K, out->codes, (float *)out->scales, (hipStream_t)stream);
     return launch_quantize_fp8_rows(w_bf16, rows, out->K, out->codes, (float *)out->scales, (hipStream_t)stream);
 }
 
@@ -227,8 +244,8 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
         set_error("qarl_qgemm_grouped: null pointer");
         return QARL_ERR_INVALID_ARG;
     }
-    if (W->fmt == QARL_FP8_E4M3_CH && !x_scales) {
-        set_error("qarl_qgemm_grouped: FP8 needs x_scales");
+    if (fp8_activations(W->fmt) && !x_scales) {
+        set_error("qarl_qgemm_grouped: e4m3 activations need x_scales");
         return QARL_ERR_INVALID_ARG;
     }
     if (!aligned16(x) || !aligned16(out)) {
@@ -258,9 +275,25 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
         use = (M <= (int64_t)W->E * 64 && qgemm_stream_supported(W->fmt, W->N, W->K)) ? QARL_PATH_DECODE : QARL_PATH_PREFILL;
     const size_t stage = ws_stage_bytes(W, M, epilogue);
     const size_t sums = (use == QARL_PATH_PREFILL) ? ws_sums_bytes(W, x_rows) : 0;
-    if (stage + sums > 0 && (!ws || ws_bytes < stage + sums || !aligned16(ws))) {
-        set_error("qarl_qgemm_grouped: this call needs %zu bytes of 16-byte aligned workspace (got %zu)", stage + sums, ws_bytes);
+    const size_t xwide = ws_xwide_bytes(W, x_rows);
+    const size_t wwide = (use == QARL_PATH_PREFILL) ? ws_wwide_bytes(W) : 0;
+    const size_t need = stage + sums + xwide + wwide;
+    if (need > 0 && (!ws || ws_bytes < need || !aligned16(ws))) {
+        set_error("qarl_qgemm_grouped: this call needs %zu bytes of 16-byte aligned workspace (got %zu)", need, ws_bytes);
         return QARL_ERR_WORKSPACE;
+    }
+    if (xwide) {   // W4A8: e4m3 rows -> the same values as bf16 rows; the kernels scale by s_x in their epilogue
+        void *x16 = (char *)ws + stage + sums;
+        rc = launch_e4m3_to_bf16(x, x_rows * (int64_t)W->K, x16, st);
+        if (rc) return rc;
+        a.x = x16;
+    }
+    if (wwide) {   // FP4 on the tiled path: e2m1 codes -> e4m3 bytes, then the FP8 kernel
+        void *c8 = (char *)ws + stage + sums + xwide;
+        rc = launch_widen_e2m1(W->codes, (int64_t)W->E * W->N * W->K, c8, st);
+        if (rc) return rc;
+        a.codes = c8;
+        a.fmt = QARL_FP8_E4M3_CH;
     }
     if (epilogue == QARL_EPI_COMBINE) {
         if (!combine_w || !sorted_pairs) {
@@ -274,7 +307,7 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
     }
     if (sums) {
         float *gs = (float *)((char *)ws + stage);
-        rc = launch_group_sums(x, x_rows, W->K, gs, st);
+        rc = launch_group_sums(a.x, x_rows, W->K, gs, st);
         if (rc) return rc;
         a.x_group_sums = gs;
     }

@@ -129,6 +129,9 @@ int raise_lds_limit(const void *kernel, LdsLimitOnce &done, const char *what);
 // Kernel launchers (one per .hip file); all validate nothing: api.hip does.
 int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *scales, hipStream_t s);
 int launch_quantize_fp8_rows(const void *x, int64_t rows, int K, void *codes, float *scales, hipStream_t s);
+int launch_quantize_fp4_rows(const void *x, int64_t rows, int K, void *codes, float *scales, hipStream_t s);
+int launch_widen_e2m1(const void *codes4, int64_t n_weights, void *codes8, hipStream_t s);   // e2m1 codes -> e4m3 bytes
+int launch_e4m3_to_bf16(const void *x8, int64_t n, void *x16, hipStream_t s);               // e4m3 bytes -> bf16 (exact)
 int launch_route_only(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w, hipStream_t s);
 int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w,
                  int32_t *counts, int32_t *offsets, int32_t *pairs, int32_t *tokens, hipStream_t s);
@@ -139,7 +142,7 @@ struct GemmArgs {
     const void *codes;
     const void *scales;
     const void *x;
-    const float *x_scales;
+    const float *x_scales;       // FP8 / FP4: scale of each activation row; W4A8: the same, applied in the epilogue
     const float *x_group_sums;   // W4A16 prefill path: -1.5 * sum of x over each 128-k group, [x_rows][K/128]
     const int32_t *row_map;      // gather of activation rows, or null
     const int32_t *out_row_map;  // scatter of output rows, or null

@@ -40,6 +40,7 @@ struct StreamParams {
     int n_units;     // pairs of 16-row weight tiles per expert
     int n_slices;    // workgroups along the weight rows of one expert
     int m_split;     // row blocks per (expert, slice) in the grid
+    int w4;          // weights are packed e2m1 codes [E][N][K/8] words
 };
 
 // LDS bytes per activation row: the row plus 16 bytes, so consecutive rows skew by 4 banks.
@@ -52,8 +53,24 @@ size_t stream_lds_bytes(int K, int MT)
     return rows * 12 + 16 + rows * x_stride(K);
 }
 
-// EPI: NONE or SILU_MUL; MT: 16-row token tiles per block; R: ring depth in 128-k steps (must divide K/128).
-template <int EPI, int MT, int R>
+// e2m1 magnitude code (3 bits) -> e4m3 byte of the same value: 0, 0.5, 1, 1.5 | 2, 3, 4, 6.  Every e2m1 value is
+// an e4m3 value, so FP4 weights are widened in registers (one byte permute per four codes) and meet the e4m3
+// token rows in the same matrix instruction as FP8 weights do.
+constexpr uint32_t kE2m1LutLo = 0x3c383000u, kE2m1LutHi = 0x4c484440u;
+
+// A word of eight packed e2m1 codes (byte b: element b in the low nibble, element 4 + b in the high nibble)
+// -> the eight e4m3 bytes in element order.
+__device__ __forceinline__ u32x2 widen_e2m1_word(uint32_t w)
+{
+    u32x2 o;
+    o[0] = __builtin_amdgcn_perm(kE2m1LutHi, kE2m1LutLo, w & 0x07070707u) | ((w & 0x08080808u) << 4);
+    o[1] = __builtin_amdgcn_perm(kE2m1LutHi, kE2m1LutLo, (w >> 4) & 0x07070707u) | (w & 0x80808080u);
+    return o;
+}
+
+// EPI: NONE or SILU_MUL; MT: 16-row token tiles per block; R: ring depth in 128-k steps (must divide K/128);
+// W4: the weights are packed e2m1 codes (half a byte per weight) instead of e4m3 bytes.
+template <int EPI, int MT, int R, bool W4>
 __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -82,7 +99,7 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamPa
     const int per_slice = (p.n_units + p.n_slices - 1) / p.n_slices;
     const int u_lo = slice * per_slice, u_hi = min(p.n_units, u_lo + per_slice);
     const int n_pairs = max(0, u_hi - u_lo);  // pairs of this workgroup; wavefronts draw them from an LDS counter
-    const int words_per_row = K / 4;
+    const int words_per_row = W4 ? K / 8 : K / 4;
     const int64_t ebase = (int64_t)e * N;
 
     auto tile_row = [&](int pi, int nt) -> int {  // weight row of this lane in tile nt of the slice's pi-th pair
@@ -91,8 +108,9 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamPa
         return u * 32 + nt * 16 + c;
     };
 
+    constexpr int kH = W4 ? 1 : 2;   // 16-byte loads per lane, tile and 128-k step: 32 weights of one row
     struct Slot {
-        u32x4 w[2][2];
+        u32x4 w[2][kH];
     };
     Slot ring[R];
     // Base pointer of the R-step batch (pair pi, steps g0..) of tile nt for this lane.  Past this
@@ -102,7 +120,7 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamPa
     auto batch_src = [&](int pi, int g0, int nt) -> const uint32_t * {
         const bool ok = pi < n_pairs;
         const int64_t row = ebase + (ok ? tile_row(pi, nt) : c);
-        return p.codes + row * words_per_row + (ok ? g0 * 32 + q * 8 : 0);
+        return p.codes + row * words_per_row + (ok ? g0 * (8 * kH * 2) + q * (4 * kH) : 0);
     };
     // Plain (temporal) loads on purpose: with row-major codes one load instruction takes half of each
     // 128-byte line it touches and the h = 1 load the other half.  A nontemporal load drops the line
@@ -112,7 +130,7 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamPa
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) dst.w[nt][h] = *(const u32x4 *)(src[nt] + r * 32 + h * 4);
+            for (int h = 0; h < kH; ++h) dst.w[nt][h] = *(const u32x4 *)(src[nt] + r * (16 * kH) + h * 4);
     };
     auto fill_ring = [&](int pi, int g0) {
         const uint32_t *src[2] = {batch_src(pi, g0, 0), batch_src(pi, g0, 1)};
@@ -190,9 +208,16 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamPa
                     Slot &cur = ring[r];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const u32x4 w0 = cur.w[0][j >> 1], w1 = cur.w[1][j >> 1];
-                        const long b0 = (long)(((uint64_t)w0[(j & 1) * 2 + 1] << 32) | w0[(j & 1) * 2]);
-                        const long b1 = (long)(((uint64_t)w1[(j & 1) * 2 + 1] << 32) | w1[(j & 1) * 2]);
+                        long b0, b1;   // the 8 weights k = 8 j .. 8 j + 7 of this lane's row in either tile
+                        if (W4) {
+                            const u32x2 e0 = widen_e2m1_word(cur.w[0][0][j]), e1 = widen_e2m1_word(cur.w[1][0][j]);
+                            b0 = (long)(((uint64_t)e0[1] << 32) | e0[0]);
+                            b1 = (long)(((uint64_t)e1[1] << 32) | e1[0]);
+                        } else {
+                            const u32x4 w0 = cur.w[0][(j >> 1) % kH], w1 = cur.w[1][(j >> 1) % kH];
+                            b0 = (long)(((uint64_t)w0[(j & 1) * 2 + 1] << 32) | w0[(j & 1) * 2]);
+                            b1 = (long)(((uint64_t)w1[(j & 1) * 2 + 1] << 32) | w1[(j & 1) * 2]);
+                        }
 #pragma unroll
                         for (int mt = 0; mt < MT; ++mt) {
                             const long a = *(const long *)(xs + (mt * 16 + c) * stride + g * 128 + q * 32 + j * 8);
@@ -234,8 +259,8 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamPa
     }
 }
 
-template <int EPI, int MT, int R>
-int launch_cfg(const StreamParams &p, hipStream_t s)
+template <int EPI, int MT, int R, bool W4>
+int launch_cfg_w(const StreamParams &p, hipStream_t s)
 {
     const size_t lds = stream_lds_bytes(p.K, MT);
     if (lds > 160 * 1024) {
@@ -243,12 +268,18 @@ int launch_cfg(const StreamParams &p, hipStream_t s)
         return QARL_ERR_UNSUPPORTED;
     }
     static LdsLimitOnce once;
-    auto kern = qgemm_stream_fp8_kernel<EPI, MT, R>;
+    auto kern = qgemm_stream_fp8_kernel<EPI, MT, R, W4>;
     if (int rc = raise_lds_limit((const void *)kern, once, "hipFuncSetAttribute(stream fp8)")) return rc;
     const int64_t units = (int64_t)p.E * p.n_slices;
     const int64_t grid = ((units + 7) / 8) * 8 * p.m_split;
     kern<<<dim3((unsigned)grid), dim3(kSThreads), lds, s>>>(p);
     return check_hip(hipGetLastError(), "qgemm_stream_fp8_kernel");
+}
+
+template <int EPI, int MT, int R>
+int launch_cfg(const StreamParams &p, hipStream_t s)
+{
+    return p.w4 ? launch_cfg_w<EPI, MT, R, true>(p, s) : launch_cfg_w<EPI, MT, R, false>(p, s);
 }
 
 template <int EPI, int MT>
@@ -279,6 +310,7 @@ int launch_one(const GemmArgs &a, hipStream_t s)
     p.N = a.N;
     p.K = a.K;
     p.out_f32 = a.out_f32;
+    p.w4 = (a.fmt == QARL_FP4_E2M1_CH);
     p.n_units = (EPI == QARL_EPI_SILU_MUL) ? (a.N / 2) / 16 : a.N / 32;
     // rows per expert the grid should cover in one pass: mean + 4 sigma of a uniform router
     const double mean = (double)a.M / (double)a.E;
@@ -307,7 +339,7 @@ int launch_one(const GemmArgs &a, hipStream_t s)
 
 bool qgemm_stream_supported(int fmt, int N, int K)
 {
-    if (fmt == QARL_W4A16_G128) return qgemm_stream_w4_supported(N, K);
+    if (fmt == QARL_W4A16_G128 || fmt == QARL_W4A8_G128) return qgemm_stream_w4_supported(N, K);
     if (N % 32 != 0 || K % kGroup != 0 || K > 4096) return false;  // the gather sweeps >= 2 rows per step
     return stream_lds_bytes(K, 1) <= 160 * 1024;
 }
@@ -319,7 +351,7 @@ int launch_qgemm_stream(const GemmArgs &a, hipStream_t s)
                   "FP8: K %% 128 == 0, K <= 4096; the token tile of one row block must fit LDS)", a.N, a.K);
         return QARL_ERR_UNSUPPORTED;
     }
-    if (a.fmt == QARL_W4A16_G128) return launch_qgemm_stream_w4(a, s);
+    if (a.fmt == QARL_W4A16_G128 || a.fmt == QARL_W4A8_G128) return launch_qgemm_stream_w4(a, s);
     return a.epilogue == QARL_EPI_SILU_MUL ? launch_one<QARL_EPI_SILU_MUL>(a, s) : launch_one<QARL_EPI_NONE>(a, s);
 }
 

@@ -49,6 +49,7 @@ struct W4Params {
     const uint32_t *codes;   // 1 KiB blocks [E*N/16][K/128][256 words]
     const uint16_t *scales;  // bf16 [E][N][K/128]
     const uint16_t *x;       // bf16 rows
+    const float *x_scales;   // W4A8: scale of each activation row (the rows of x then hold e4m3 values), else null
     const int32_t *row_map;
     const int32_t *out_row_map;
     const int32_t *offsets;
@@ -405,6 +406,11 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_kernel(W4Params p
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
                     const i32x4 orow4 = *(const i32x4 *)(s_orow + mt * 32 + 8 * i4 + 4 * h);
+                    if (p.x_scales) {   // W4A8: the row scale s_x of eq. (2), in front of SiLU
+                        const i32x4 xrow4 = *(const i32x4 *)(s_row + mt * 32 + 8 * i4 + 4 * h);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[mt][i4 * 4 + i] *= p.x_scales[xrow4[i]];
+                    }
                     if (kSilu) {
                         // Registers i and i+1 trade 16-lane rows: afterwards every lane holds a gate value and the
                         // up value of the same column; lanes of the first tile for row i, of the second for row i+1.
@@ -482,6 +488,7 @@ int launch_one(const GemmArgs &a, hipStream_t s)
     p.codes = (const uint32_t *)a.codes;
     p.scales = (const uint16_t *)a.scales;
     p.x = (const uint16_t *)a.x;
+    p.x_scales = a.fmt == QARL_W4A8_G128 ? a.x_scales : nullptr;
     p.row_map = a.row_map;
     p.out_row_map = a.out_row_map;
     p.offsets = a.offsets;

@@ -35,6 +35,7 @@ struct TileParams {
     const void *scales;
     const void *x;
     const float *x_group_sums;
+    const float *x_scales;   // W4A8: scale of each activation row (x then holds e4m3 values as bf16), else null
     const int32_t *row_map;
     const int32_t *out_row_map;
     const int32_t *offsets;
@@ -57,6 +58,7 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
     constexpr int kBufBytes = kBM * kStride + kBM * 4;  // tile + per-row group sums
     __shared__ __attribute__((aligned(16))) int s_rows[kBM];   // activation row of each tile row (clamped to a valid one)
     __shared__ __attribute__((aligned(16))) int s_orow[kBM];   // output row, -1 past the expert's last row
+    __shared__ __attribute__((aligned(16))) float s_xsc[kBM];  // W4A8: row scale s_x (1 otherwise)
 
     const int tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
@@ -109,6 +111,7 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
         const int xrow = p.row_map ? p.row_map[i] : i;
         s_rows[tid] = xrow;
         s_orow[tid] = tid < mrem ? (p.out_row_map ? p.out_row_map[i] : i) : -1;
+        s_xsc[tid] = p.x_scales ? p.x_scales[xrow] : 1.f;
     }
     lds_barrier();
 
@@ -255,7 +258,8 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
                     const u32x2 sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(vv[2 * ip]),
                                                                       __float_as_uint(vv[2 * ip + 1]), false, false);
                     const int row = ms * 32 + 8 * i4 + 4 * h + 2 * ip + (c >> 4);
-                    const float a = silu_mul_f32(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                    const float rs = s_xsc[row];
+                    const float a = silu_mul_f32(__uint_as_float(sw[0]) * rs, __uint_as_float(sw[1]) * rs);
                     ot[row * (kBN / 2) + wn * 16 + (c & 15)] = f32_to_bf16_hw(a);
                 }
             }
@@ -287,8 +291,9 @@ __global__ __launch_bounds__(kTileThreads, MS == 2 ? 4 : 2) void qgemm_tile_kern
                 f32x4 vv;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) vv[i] = acc[ms][i4 * 4 + i];
+                const f32x4 rs4 = *(const f32x4 *)(s_xsc + ms * 32 + 8 * i4 + 4 * h);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ot[(8 * i4 + 4 * h + i) * 32 + c] = vv[i];
+                for (int i = 0; i < 4; ++i) ot[(8 * i4 + 4 * h + i) * 32 + c] = vv[i] * rs4[i];
             }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
@@ -335,6 +340,7 @@ static int launch_cfg(const GemmArgs &a, hipStream_t s)
     p.scales = a.scales;
     p.x = a.x;
     p.x_group_sums = a.x_group_sums;
+    p.x_scales = a.fmt == QARL_W4A8_G128 ? a.x_scales : nullptr;
     p.row_map = a.row_map;
     p.out_row_map = a.out_row_map;
     p.offsets = a.offsets;
@@ -397,7 +403,7 @@ int launch_group_sums(const void *x_bf16, int64_t rows, int K, float *sums, hipS
 
 int launch_qgemm_tile(const GemmArgs &a, hipStream_t s)
 {
-    if (a.fmt == QARL_W4A16_G128)
+    if (a.fmt == QARL_W4A16_G128 || a.fmt == QARL_W4A8_G128)
         return a.epilogue == QARL_EPI_SILU_MUL ? launch_one<QARL_EPI_SILU_MUL>(a, s) : launch_one<QARL_EPI_NONE>(a, s);
     return launch_qgemm_tile_fp8(a, s);
 }

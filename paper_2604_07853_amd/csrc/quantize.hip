@@ -119,11 +119,25 @@ int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *
     return check_hip(hipGetLastError(), "quantize_int4_kernel");
 }
 
-// ------------------------------------------------------------------- fp8 --
+// ------------------------------------------------------------- fp8 / fp4 --
+// FP4 = true: the same FP Quant with alpha = 6 into e2m1 codes, eight per 32-bit word (byte b of the word: element
+// b in the low nibble, element 4 + b in the high nibble).
 // One wavefront per row; rows of up to 4096 elements are read once and wait in registers between the absmax
 // pass and the conversion pass, longer rows are read a second time (a cache hit).
 constexpr int kF8Threads = 256;
 
+// e2m1 code of a finite t, nearest value with ties to the even code, saturating at 6: the magnitude code is the
+// number of rounding boundaries at or below |t| (midpoints 0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5; a tie belongs to
+// the upper value exactly where that one has the even code).
+__device__ __forceinline__ uint32_t e2m1_from_f32(float t)
+{
+    const float a = fabsf(t);
+    const uint32_t m = (uint32_t)(a > 0.25f) + (uint32_t)(a >= 0.75f) + (uint32_t)(a > 1.25f) + (uint32_t)(a >= 1.75f) +
+                       (uint32_t)(a > 2.5f) + (uint32_t)(a >= 3.5f) + (uint32_t)(a > 5.0f);
+    return m | ((__float_as_uint(t) >> 28) & 8u);
+}
+
+template <bool FP4>
 __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uint16_t *__restrict__ x,
                                                                        int64_t rows, int K,
                                                                        uint8_t *__restrict__ codes,
@@ -164,9 +178,10 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
         }
     }
     am = wave_max(am);
-    const float s = am / 448.0f;
+    const float s = am / (FP4 ? 6.0f : 448.0f);
     if (lane == 0) scales[row] = s;
-    u32x2 *cr = (u32x2 *)(codes + row * K);
+    u32x2 *cr = (u32x2 *)(codes + row * K);           // e4m3: 8 bytes per 8 elements
+    uint32_t *cr4 = (uint32_t *)(codes + row * (K / 2));  // e2m1: 4 bytes per 8 elements
     // x / s, correctly rounded, without a divide per element: with y = RN(1 / s) (one IEEE divide per row),
     // q0 = RN(x y) and the exact remainder r = x - q0 s from one FMA, RN(q0 + r y) is the correctly rounded
     // quotient (Markstein's correction step; it needs the correctly rounded reciprocal and no underflow on the
@@ -182,6 +197,21 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
     };
     auto convert = [&](const u32x4 v, int c) {
         u32x2 o = {0, 0};
+        if (FP4) {
+            uint32_t w = 0;
+            if (s != 0.f) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {   // elements 2i and 2i+1; element e sits in nibble (e & 3) * 2 + (e >> 2)
+                    const uint32_t c0 = e2m1_from_f32(div(__uint_as_float(v[i] << 16)));
+                    const uint32_t c1 = e2m1_from_f32(div(__uint_as_float(v[i] & 0xffff0000u)));
+                    const int e0 = 2 * i, e1 = 2 * i + 1;
+                    w |= c0 << (4 * ((e0 & 3) * 2 + (e0 >> 2)));
+                    w |= c1 << (4 * ((e1 & 3) * 2 + (e1 >> 2)));
+                }
+            }
+            cr4[c] = w;
+            return;
+        }
         if (s != 0.f) {
             // v_cvt_pk_fp8_f32 rounds to nearest even into OCP e4m3 (subnormals included) exactly like
             // e4m3_from_f32 for every finite |t| <= 448 (checked over all 2^32 bit patterns on gfx950); the
@@ -220,9 +250,84 @@ int launch_quantize_fp8_rows(const void *x, int64_t rows, int K, void *codes, fl
         set_error("quantize_fp8: %lld blocks exceed the grid limit", (long long)blocks);
         return QARL_ERR_UNSUPPORTED;
     }
-    quantize_fp8_rows_kernel<<<dim3((unsigned)blocks), dim3(kF8Threads), 0, s>>>(
+    quantize_fp8_rows_kernel<false><<<dim3((unsigned)blocks), dim3(kF8Threads), 0, s>>>(
         (const uint16_t *)x, rows, K, (uint8_t *)codes, scales);
     return check_hip(hipGetLastError(), "quantize_fp8_rows_kernel");
+}
+
+int launch_quantize_fp4_rows(const void *x, int64_t rows, int K, void *codes, float *scales, hipStream_t s)
+{
+    if (rows == 0) return QARL_OK;
+    const int per_block = kF8Threads / 64;
+    const int64_t blocks = (rows + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffLL) {
+        set_error("quantize_fp4: %lld blocks exceed the grid limit", (long long)blocks);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    quantize_fp8_rows_kernel<true><<<dim3((unsigned)blocks), dim3(kF8Threads), 0, s>>>(
+        (const uint16_t *)x, rows, K, (uint8_t *)codes, scales);
+    return check_hip(hipGetLastError(), "quantize_fp4_rows_kernel");
+}
+
+// ---- format bridges of the 4-bit-weight x 8-bit-activation schemes.
+// e2m1 codes -> the e4m3 bytes of the same values (every e2m1 value is an e4m3 value): lets the FP8 tiled kernel
+// run on FP4 weights.  One thread per word of eight codes.
+__global__ __launch_bounds__(256) void widen_e2m1_kernel(const uint32_t *__restrict__ src, int64_t n_words,
+                                                         u32x2 *__restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_words) return;
+    const uint32_t w = src[i];
+    const uint32_t lo = 0x3c383000u, hi = 0x4c484440u;   // magnitude code -> e4m3 byte: 0, .5, 1, 1.5 | 2, 3, 4, 6
+    u32x2 o;
+    o[0] = __builtin_amdgcn_perm(hi, lo, w & 0x07070707u) | ((w & 0x08080808u) << 4);
+    o[1] = __builtin_amdgcn_perm(hi, lo, (w >> 4) & 0x07070707u) | (w & 0x80808080u);
+    dst[i] = o;
+}
+
+int launch_widen_e2m1(const void *codes4, int64_t n_weights, void *codes8, hipStream_t s)
+{
+    const int64_t n_words = n_weights / 8;
+    if (n_words == 0) return QARL_OK;
+    const int64_t blocks = (n_words + 255) / 256;
+    if (blocks > 0x7fffffffLL) {
+        set_error("widen e2m1: grid too large");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    widen_e2m1_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const uint32_t *)codes4, n_words, (u32x2 *)codes8);
+    return check_hip(hipGetLastError(), "widen_e2m1_kernel");
+}
+
+// e4m3 bytes -> the bf16 values they stand for (exact: four significant bits): lets the W4A16 kernels run on
+// e4m3 activations, whose row scale they apply in the epilogue.  One thread per 8 bytes.
+__global__ __launch_bounds__(256) void e4m3_to_bf16_kernel(const u32x2 *__restrict__ src, int64_t n8,
+                                                           u32x4 *__restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    const u32x2 v = src[i];
+    u32x4 o;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const float f0 = __builtin_amdgcn_cvt_f32_fp8((int)v[h], 0), f1 = __builtin_amdgcn_cvt_f32_fp8((int)v[h], 1);
+        const float f2 = __builtin_amdgcn_cvt_f32_fp8((int)v[h], 2), f3 = __builtin_amdgcn_cvt_f32_fp8((int)v[h], 3);
+        o[2 * h] = (__float_as_uint(f0) >> 16) | (__float_as_uint(f1) & 0xffff0000u);       // exact: low 16 bits are zero
+        o[2 * h + 1] = (__float_as_uint(f2) >> 16) | (__float_as_uint(f3) & 0xffff0000u);
+    }
+    dst[i] = o;
+}
+
+int launch_e4m3_to_bf16(const void *x8, int64_t n, void *x16, hipStream_t s)
+{
+    const int64_t n8 = n / 8;
+    if (n8 == 0) return QARL_OK;
+    const int64_t blocks = (n8 + 255) / 256;
+    if (blocks > 0x7fffffffLL) {
+        set_error("e4m3 -> bf16: grid too large");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    e4m3_to_bf16_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x2 *)x8, n8, (u32x4 *)x16);
+    return check_hip(hipGetLastError(), "e4m3_to_bf16_kernel");
 }
 
 }  // namespace qarl
