@@ -109,6 +109,19 @@ size_t qarl_logprob_workspace_bytes(int T, int H, int V);
  * Errors: INVALID_ARG (null pointers, E/N/K <= 0, wrong group), ALIGNMENT, UNSUPPORTED. */
 int qarl_quantize_weights(const void *w_bf16, const qarl_qweight *out, void *stream);
 
+/* Sizes of the two buffers of a qarl_qweight, in bytes (0 for an unknown format or non-positive sizes). */
+size_t qarl_codes_bytes(int fmt, int E, int N, int K);
+size_t qarl_scales_bytes(int fmt, int E, int N, int K);
+
+/* The codes of W in a layout-free form, for a consumer outside this library (section 3.1, item 3: the low-bit
+ * tensors the learner materialises are what is published to the rollout engine).  The GEMM kernels read the 4-bit
+ * formats in a blocked, bit-permuted packing; this call writes the plain one:
+ *   W4A16_G128 / W4A8_G128: uint32 [E][N][K/8], element i of a word (k = 8 * word + i) in bits [4i, 4i+3] as q + 8;
+ *   FP4_E2M1_CH:            uint32 [E][N][K/8], element i in bits [4i, 4i+3] as the e2m1 code;
+ *   FP8_E4M3_CH:            uint8  [E][N][K], a copy (the format is stored this way).
+ * codes_out: qarl_codes_bytes(...) bytes, 16-byte aligned.  Scales need no conversion. */
+int qarl_codes_to_canonical(const qarl_qweight *W, void *codes_out, void *stream);
+
 /* FP Quant of section 2.2 with one scale per row, for activations (the s_x of eq. (2)):
  * x bf16 [rows][K] -> codes uint8 [rows][K], scales float [rows].  K % 8 == 0. */
 int qarl_quantize_rows_fp8(const void *x_bf16, int64_t rows, int K, void *codes, float *scales,

@@ -177,6 +177,35 @@ def qgemm_w4a16(x_bits, codes, scales, offsets, row_map=None, group=128, acc32=F
     return out
 
 
+def qgemm_w4a16_dx(dy_bits, codes, scales, offsets, group=128):
+    """Input gradient of the grouped W4A16 GEMM under the straight-through estimator: dy bf16 bits [M, N] in the
+    forward's output row order -> float64 [M, K]."""
+    dy = _c(dy_bits, np.uint16)
+    codes = _c(codes, np.uint32)
+    scales = _c(scales, np.uint16)
+    offsets = _c(offsets, np.int32)
+    E, N, K8 = codes.shape
+    K = K8 * 8
+    M = int(offsets[-1])
+    out = np.zeros((M, K), dtype=np.float64)
+    lib().oracle_qgemm_w4a16_dx(_p(dy), C.c_int(K), C.c_int64(M), _p(offsets), C.c_int(E), _p(codes), _p(scales),
+                                C.c_int(N), C.c_int(group), _p(out))
+    return out
+
+
+def grouped_dw(dy_bits, x_bits, offsets, E, row_map=None):
+    """Weight gradient (passed straight to the masters): float64 [E, N, K] = sum over the expert's rows of dy^T x."""
+    dy = _c(dy_bits, np.uint16)
+    x = _c(x_bits, np.uint16)
+    offsets = _c(offsets, np.int32)
+    M, N = dy.shape
+    K = x.shape[1]
+    rm = None if row_map is None else _c(row_map, np.int32)
+    out = np.zeros((E, N, K), dtype=np.float64)
+    lib().oracle_grouped_dw(_p(dy), _p(x), C.c_int(K), _p(rm), C.c_int64(M), _p(offsets), C.c_int(E), C.c_int(N), _p(out))
+    return out
+
+
 def qgemm_fp8(xq, sx, wq, sw, offsets, row_map=None):
     xq = _c(xq, np.uint8)
     sx = _c(sx, np.float32)

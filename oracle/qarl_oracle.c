@@ -338,6 +338,52 @@ void oracle_qgemm_w4a16(const uint16_t *x, int K, const int32_t *row_map, int64_
     (void)M;
 }
 
+/* Backward of eq. (1) under the straight-through estimator (section 3.1, item 2: the forward runs on the low-bit
+ * weights, gradients are taken as if Quant were the identity and applied to the BF16 masters).  With
+ * Y[i] = What_e x[row(i)] the two gradients are
+ *     dX[i][k]    = sum_n dY[i][n] * What_e[n][k]                  (the input gradient sees the dequantized weight),
+ *     dW[e][n][k] = sum_{i in expert e} dY[i][n] * x[row(i)][k]    (the weight gradient passes straight to the master),
+ * dY bf16 [M][N] in the row order of the forward's output, everything accumulated in double. */
+void oracle_qgemm_w4a16_dx(const uint16_t *dy, int K, int64_t M, const int32_t *offsets, int E,
+                           const uint32_t *codes, const uint16_t *scales, int N, int group, double *dx)
+{
+    float *wd = (float *)malloc(sizeof(float) * (size_t)N * K);
+    for (int e = 0; e < E; ++e) {
+        int64_t lo = offsets[e], hi = offsets[e + 1];
+        if (hi <= lo) continue;
+        oracle_dequant_int4(codes + (int64_t)e * N * (K / 8),
+                            scales + (int64_t)e * N * (K / group), N, K, group, wd);
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t i = lo; i < hi; ++i)
+            for (int k = 0; k < K; ++k) {
+                double a = 0.0;
+                for (int n = 0; n < N; ++n) a += (double)bf16_to_f32(dy[i * N + n]) * (double)wd[(int64_t)n * K + k];
+                dx[i * K + k] = a;
+            }
+    }
+    free(wd);
+    (void)M;
+}
+
+void oracle_grouped_dw(const uint16_t *dy, const uint16_t *x, int K, const int32_t *row_map, int64_t M,
+                       const int32_t *offsets, int E, int N, double *dw)
+{
+    for (int e = 0; e < E; ++e) {
+        int64_t lo = offsets[e], hi = offsets[e + 1];
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int n = 0; n < N; ++n)
+            for (int k = 0; k < K; ++k) {
+                double a = 0.0;
+                for (int64_t i = lo; i < hi; ++i) {
+                    int64_t r = row_map ? (int64_t)row_map[i] : i;
+                    a += (double)bf16_to_f32(dy[i * N + n]) * (double)bf16_to_f32(x[r * K + k]);
+                }
+                dw[((int64_t)e * N + n) * K + k] = a;
+            }
+    }
+    (void)M;
+}
+
 /* eq. (2): Y[i][n] = s_x[row] * s_w[e][n] * sum_k x_q[row][k] * w_q[e][n][k]. */
 void oracle_qgemm_fp8(const uint8_t *xq, const float *sx, int K, const int32_t *row_map,
                       int64_t M, const int32_t *offsets, int E, const uint8_t *wq,

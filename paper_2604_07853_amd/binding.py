@@ -22,11 +22,11 @@ QARL_PATH_AUTO, QARL_PATH_DECODE, QARL_PATH_PREFILL = 0, 1, 2
 QARL_EPI_NONE, QARL_EPI_SILU_MUL, QARL_EPI_COMBINE = 0, 1, 2
 QARL_OUT_BF16, QARL_OUT_F32 = 0, 1
 
-# the first four return a string or a size, the rest a qarl_status
+# the first six return a string or a size, the rest a qarl_status
 EXPORTS = ["qarl_last_error", "qarl_qgemm_workspace_bytes", "qarl_logprob_workspace_bytes",
-           "qarl_token_logprob_static_limit", "qarl_quantize_weights", "qarl_quantize_rows_fp8", "qarl_moe_route", "qarl_qgemm_grouped",
+           "qarl_token_logprob_static_limit", "qarl_codes_bytes", "qarl_scales_bytes", "qarl_quantize_weights", "qarl_quantize_rows_fp8", "qarl_moe_route", "qarl_qgemm_grouped",
            "qarl_qgemm_routed", "qarl_token_logprob", "qarl_logprob_mismatch", "qarl_tbpo_objective",
-           "qarl_token_logprob_static"]
+           "qarl_token_logprob_static", "qarl_codes_to_canonical"]
 
 
 class QarlError(RuntimeError):
@@ -71,12 +71,16 @@ def lib():
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.qarl_tbpo_objective.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
                                           C.c_float, C.c_float, C.c_float, C.c_float, C.c_float] + [C.c_void_p] * 8
+        for fn in (L.qarl_codes_bytes, L.qarl_scales_bytes):
+            fn.restype = C.c_size_t
+            fn.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int]
+        L.qarl_codes_to_canonical.argtypes = [C.POINTER(qarl_qweight), C.c_void_p, C.c_void_p]
         L.qarl_token_logprob_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                                 C.c_void_p, C.c_void_p, C.c_void_p]
         L.qarl_token_logprob_static_limit.restype = C.c_size_t
         L.qarl_token_logprob_static_limit.argtypes = []
-        for name in EXPORTS[4:]:
+        for name in EXPORTS[6:]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -125,6 +129,18 @@ def qarl_quantize_weights(w, fmt=QARL_W4A16_G128, out=None):
     if out is None:
         out = QWeight.empty(fmt, E, N, K, w.device)
     _check(lib().qarl_quantize_weights(_ptr(w), C.byref(out.desc), _stream()))
+    return out
+
+
+def qarl_codes_to_canonical(W, out=None):
+    """Codes of W in the layout-free packing of include/qarl.h: int32 words [E, N, K/8] (4-bit formats) or uint8 [E, N, K]."""
+    if out is None:
+        if W.fmt == QARL_FP8_E4M3_CH:
+            out = torch.empty((W.E, W.N, W.K), dtype=torch.uint8, device=W.codes.device)
+        else:
+            out = torch.empty((W.E, W.N, W.K // 8), dtype=torch.int32, device=W.codes.device)
+    assert out.numel() * out.element_size() == lib().qarl_codes_bytes(W.fmt, W.E, W.N, W.K)
+    _check(lib().qarl_codes_to_canonical(C.byref(W.desc), _ptr(out), _stream()))
     return out
 
 

@@ -142,6 +142,46 @@ int qarl_quantize_weights(const void *w_bf16, const qarl_qweight *out, void *str
     return launch_quantize_fp8_rows(w_bf16, rows, out->K, out->codes, (float *)out->scales, (hipStream_t)stream);
 }
 
+size_t qarl_codes_bytes(int fmt, int E, int N, int K)
+{
+    if (E <= 0 || N <= 0 || K <= 0) return 0;
+    const size_t n = (size_t)E * (size_t)N * (size_t)K;
+    if (fmt == QARL_FP8_E4M3_CH) return n;
+    if (fmt == QARL_W4A16_G128 || fmt == QARL_W4A8_G128 || fmt == QARL_FP4_E2M1_CH) return n / 2;
+    return 0;
+}
+
+size_t qarl_scales_bytes(int fmt, int E, int N, int K)
+{
+    if (E <= 0 || N <= 0 || K <= 0) return 0;
+    if (fmt == QARL_W4A16_G128 || fmt == QARL_W4A8_G128) return (size_t)E * N * (size_t)(K / 128) * 2;
+    if (fmt == QARL_FP8_E4M3_CH || fmt == QARL_FP4_E2M1_CH) return (size_t)E * N * sizeof(float);
+    return 0;
+}
+
+int qarl_codes_to_canonical(const qarl_qweight *W, void *codes_out, void *stream)
+{
+    int rc = check_qweight(W, "qarl_codes_to_canonical");
+    if (rc) return rc;
+    if (!codes_out) {
+        set_error("qarl_codes_to_canonical: null output");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!aligned16(codes_out)) {
+        set_error("qarl_codes_to_canonical: output must be 16-byte aligned");
+        return QARL_ERR_ALIGNMENT;
+    }
+    const int64_t rows = (int64_t)W->E * W->N;
+    if (W->fmt == QARL_FP8_E4M3_CH)   // stored canonically already: a plain copy
+        return check_hip(hipMemcpyAsync(codes_out, W->codes, (size_t)rows * W->K, hipMemcpyDeviceToDevice, (hipStream_t)stream),
+                         "hipMemcpyAsync(codes)");
+    if (int4_weights(W->fmt) && W->N % 16 != 0) {
+        set_error("qarl_codes_to_canonical: N %% 16 == 0 required");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    return launch_canonical_codes(W->fmt, W->codes, rows, W->K, codes_out, (hipStream_t)stream);
+}
+
 int qarl_quantize_rows_fp8(const void *x_bf16, int64_t rows, int K, void *codes, float *scales, void *stream)
 {
     if (rows < 0 || K <= 0) {

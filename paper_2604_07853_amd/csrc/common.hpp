@@ -130,6 +130,7 @@ int raise_lds_limit(const void *kernel, LdsLimitOnce &done, const char *what);
 int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *scales, hipStream_t s);
 int launch_quantize_fp8_rows(const void *x, int64_t rows, int K, void *codes, float *scales, hipStream_t s);
 int launch_quantize_fp4_rows(const void *x, int64_t rows, int K, void *codes, float *scales, hipStream_t s);
+int launch_canonical_codes(int fmt, const void *codes, int64_t rows, int K, void *out, hipStream_t s);
 int launch_widen_e2m1(const void *codes4, int64_t n_weights, void *codes8, hipStream_t s);   // e2m1 codes -> e4m3 bytes
 int launch_e4m3_to_bf16(const void *x8, int64_t n, void *x16, hipStream_t s);               // e4m3 bytes -> bf16 (exact)
 int launch_route_only(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w, hipStream_t s);

@@ -269,6 +269,51 @@ int launch_quantize_fp4_rows(const void *x, int64_t rows, int K, void *codes, fl
     return check_hip(hipGetLastError(), "quantize_fp4_rows_kernel");
 }
 
+// ---- canonical view of the packed 4-bit codes, for consumers outside this library (the low-bit tensors of section
+// 3.1 are published to the rollout engine after every update): row-major words [rows][K/8], element i of a word
+// in bits [4i, 4i+3].  int4: offset-binary q + 8 (the library's own layout is 1 KiB blocks of 16 rows x 128 k with
+// the elements of a word at the bit positions int4_bit_pos gives); e2m1: the code itself (the library packs element
+// b and 4 + b into byte b).  One thread per output word.
+template <bool FP4>
+__global__ __launch_bounds__(256) void canonical_codes_kernel(const uint32_t *__restrict__ src, int64_t rows, int K,
+                                                              uint32_t *__restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int wpr = K / 8;
+    if (i >= rows * wpr) return;
+    const int64_t row = i / wpr;
+    const int kw = (int)(i - row * wpr);   // word of the row: k in [8 kw, 8 kw + 8)
+    uint32_t w, o = 0;
+    if (FP4) {
+        w = src[i];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o |= ((w >> (4 * ((e & 3) * 2 + (e >> 2)))) & 15u) << (4 * e);
+    } else {
+        // block (row / 16, g = kw / 16): [4 = (k % 128) / 32][16 = row % 16][4 = (k % 32) / 8] words
+        const int G = K / kGroup, g = kw >> 4, q = (kw >> 2) & 3, j = kw & 3;
+        w = src[((row >> 4) * G + g) * 256 + q * 64 + (row & 15) * 4 + j];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o |= (__builtin_rotateright32(w, int4_bit_pos(e)) & 15u) << (4 * e);
+    }
+    dst[i] = o;
+}
+
+int launch_canonical_codes(int fmt, const void *codes, int64_t rows, int K, void *out, hipStream_t s)
+{
+    const int64_t n = rows * (K / 8);
+    if (n == 0) return QARL_OK;
+    const int64_t blocks = (n + 255) / 256;
+    if (blocks > 0x7fffffffLL) {
+        set_error("canonical codes: grid too large");
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (fmt == QARL_FP4_E2M1_CH)
+        canonical_codes_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const uint32_t *)codes, rows, K, (uint32_t *)out);
+    else
+        canonical_codes_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const uint32_t *)codes, rows, K, (uint32_t *)out);
+    return check_hip(hipGetLastError(), "canonical_codes_kernel");
+}
+
 // ---- format bridges of the 4-bit-weight x 8-bit-activation schemes.
 // e2m1 codes -> the e4m3 bytes of the same values (every e2m1 value is an e4m3 value): lets the FP8 tiled kernel
 // run on FP4 weights.  One thread per word of eight codes.

@@ -144,3 +144,27 @@ def test_moe_layer_stage_wise(q, oracle, fmt, path):
     layer = q.MoELayer(qgu, qdn, T, topk, path)
     out2 = layer.forward(x.cuda(), lg.cuda())
     assert np.array_equal(np_bits(out2), np_bits(out_gpu))
+
+
+def test_codes_to_canonical_equals_the_oracles_packing(q, oracle):
+    """qarl_codes_to_canonical undoes the library's blocked / bit-permuted packings on the device: its output is the
+    oracle's own row-major words (int4: q + 8 in nibble i; e2m1: the code in nibble i; e4m3: the bytes)."""
+    E, N, K = 3, 96, 512
+    w = synth.normal_bf16((E, N, K), 0.02, seed=71)
+    c4, _ = oracle.quantize_int4(np_bits(w))
+    for fmt in (q.QARL_W4A16_G128, q.QARL_W4A8_G128):
+        qw = q.qarl_quantize_weights(w.cuda(), fmt)
+        got = q.qarl_codes_to_canonical(qw).cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, c4)
+        assert q.lib().qarl_codes_bytes(fmt, E, N, K) == c4.nbytes and q.lib().qarl_scales_bytes(fmt, E, N, K) == E * N * (K // 128) * 2
+    f4, _ = oracle.quantize_fp4_rows(np_bits(w))                          # one code per byte
+    want = np.zeros((E, N, K // 8), dtype=np.uint32)
+    for i in range(8):
+        want |= f4.reshape(E, N, K // 8, 8)[..., i].astype(np.uint32) << np.uint32(4 * i)
+    q4 = q.qarl_quantize_weights(w.cuda(), q.QARL_FP4_E2M1_CH)
+    assert np.array_equal(q.qarl_codes_to_canonical(q4).cpu().numpy().view(np.uint32), want)
+    f8, _ = oracle.quantize_fp8_rows(np_bits(w))
+    q8 = q.qarl_quantize_weights(w.cuda(), q.QARL_FP8_E4M3_CH)
+    assert np.array_equal(q.qarl_codes_to_canonical(q8).cpu().numpy(), f8)
+    assert q.lib().qarl_codes_bytes(q.QARL_FP8_E4M3_CH, E, N, K) == E * N * K
+    assert q.lib().qarl_codes_bytes(99, E, N, K) == 0
