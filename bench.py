@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the other rows to time: quantize, prefill (with the LM head and the "
-                         "sequence objective), dense, fp8, stack; default all")
+                         "sequence objective), backward, dense, fp8, stack; default all")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--sweep-layers", type=int, default=48)
     ap.add_argument("--calibrate", action="store_true",
@@ -304,6 +304,27 @@ def main():
             extra["tbpo_objective_8x2048"] = {"ms": round(ms_tb, 4), "GB/s": round(tb_bytes / ms_tb / 1e6, 1),
                                               "bytes": tb_bytes, "launches": 2}
             del wlm, ws, lp_layer, xp
+
+        if on("backward"):
+            # straight-through backward of the gate_up projection at the training-forward shape (16 384 tokens, Zipf):
+            # dX = dY What (128 x 128 tiles, 16-bit operands) and dW = dY^T X
+            Tb = 16384
+            Mb = Tb * TOPK
+            lgb = synth.router_logits(Tb, E, seed=31, device=dev, zipf_s=1.1)
+            rb = q.qarl_moe_route(lgb, TOPK)
+            xb = synth.normal_bf16((Tb, H), 1.0, seed=33, device=dev)
+            dyb = synth.normal_bf16((Mb, 2 * I), 1.0, seed=34, device=dev)
+            dxb = torch.empty((Mb, H), dtype=torch.bfloat16, device=dev)
+            dwb = torch.empty((E, 2 * I, H), dtype=torch.bfloat16, device=dev)
+            ms_dx = timed(lambda: q.qarl_qgemm_grouped_dx(layers[0].gu, dyb, rb.offsets, Mb, out=dxb), 5, 1)
+            ms_dw = timed(lambda: q.qarl_grouped_dw(dyb, xb, rb.offsets, E, row_map=rb.tokens, out=dwb), 5, 1)
+            fl_b = 2 * Mb * 2 * I * H
+            extra["backward_gate_up_16384tok_zipf"] = {
+                "dx_ms": round(ms_dx, 4), "dx_TFLOP/s": round(fl_b / ms_dx / 1e9, 1),
+                "dx_frac_mfma_bf16": round(fl_b / ms_dx / 1e9 / MFMA_BF16_PEAK_TF, 4),
+                "dw_ms": round(ms_dw, 4), "dw_TFLOP/s": round(fl_b / ms_dw / 1e9, 1),
+                "dw_frac_mfma_bf16": round(fl_b / ms_dw / 1e9 / MFMA_BF16_PEAK_TF, 4)}
+            del xb, dyb, dxb, dwb, rb
 
         if on("dense"):
             # a dense SiLU-gated MLP of a second model shape (hidden 4096, intermediate 12288) through the same calls

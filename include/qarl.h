@@ -165,6 +165,22 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
                        int topk, void *out, int out_dtype, int path, void *ws, size_t ws_bytes,
                        void *stream);
 
+/* Backward of qarl_qgemm_grouped (W4A16, epilogue NONE) under the straight-through estimator of section 3.1, item 2:
+ * the forward ran on What = s*q; the gradients are those of Y[i] = What_e x[row_map[i]] with Quant treated as the
+ * identity, computed in the trainer's 16-bit precision with fp32 accumulation and meant for the BF16 masters.
+ *   qarl_qgemm_grouped_dx:  dx[o(i)][k] = sum_n dy[i][n] * What_e[n][k],  e the expert of row i, o(i) = out_row_map[i]
+ *       (i if NULL).  dy bf16 [M][N] in the forward's output row order, dx [M][K] bf16 or fp32.  The scaled gradient
+ *       dy[i][n] * s[n][k/128] is rounded to bf16 once before it meets the exact integer codes (so a one-hot dy
+ *       returns a row of s*q exactly).  Supported: E <= 256, N % 128 == 0, N <= 8192.
+ *   qarl_grouped_dw:        dw[e][n][k] = sum over the rows i of expert e of dy[i][n] * x[row_map[i]][k]
+ *       (bf16 x bf16 products, fp32 sums; experts without rows get zeros).  dw [E][N][K] bf16 or fp32.
+ *       Supported: N % 128 == 0, K % 128 == 0.
+ * Errors: INVALID_ARG, ALIGNMENT, UNSUPPORTED.  M == 0: dx is a no-op, dw is all zeros. */
+int qarl_qgemm_grouped_dx(const qarl_qweight *W, const void *dy_bf16, const int32_t *expert_offsets, int64_t M,
+                          const int32_t *out_row_map, void *dx, int out_dtype, void *stream);
+int qarl_grouped_dw(const void *dy_bf16, const void *x_bf16, const int32_t *row_map, const int32_t *expert_offsets,
+                    int64_t M, int E, int N, int K, void *dw, int out_dtype, void *stream);
+
 /* The same contraction driven by the router's ids directly, for decode-sized batches (section 4.1's
  * rollout regime: a few hundred tokens over all experts), so that no grouping pass sits between the
  * router and the expert GEMMs: problem row pr = t*topk + slot, pr in [0, T*topk), multiplies expert

@@ -26,7 +26,8 @@ QARL_OUT_BF16, QARL_OUT_F32 = 0, 1
 EXPORTS = ["qarl_last_error", "qarl_qgemm_workspace_bytes", "qarl_logprob_workspace_bytes",
            "qarl_token_logprob_static_limit", "qarl_codes_bytes", "qarl_scales_bytes", "qarl_quantize_weights", "qarl_quantize_rows_fp8", "qarl_moe_route", "qarl_qgemm_grouped",
            "qarl_qgemm_routed", "qarl_token_logprob", "qarl_logprob_mismatch", "qarl_tbpo_objective",
-           "qarl_token_logprob_static", "qarl_codes_to_canonical"]
+           "qarl_token_logprob_static", "qarl_codes_to_canonical", "qarl_qgemm_grouped_dx",
+           "qarl_grouped_dw"]
 
 
 class QarlError(RuntimeError):
@@ -75,6 +76,10 @@ def lib():
             fn.restype = C.c_size_t
             fn.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int]
         L.qarl_codes_to_canonical.argtypes = [C.POINTER(qarl_qweight), C.c_void_p, C.c_void_p]
+        L.qarl_qgemm_grouped_dx.argtypes = [C.POINTER(qarl_qweight), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                            C.c_void_p, C.c_int, C.c_void_p]
+        L.qarl_grouped_dw.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                      C.c_void_p, C.c_int, C.c_void_p]
         L.qarl_token_logprob_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                                 C.c_void_p, C.c_void_p, C.c_void_p]
@@ -231,6 +236,26 @@ def qarl_qgemm_routed(W, x, topk_ids, T, topk, x_per_token, epilogue=QARL_EPI_NO
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(lib().qarl_qgemm_routed(C.byref(W.desc), _ptr(x), int(bool(x_per_token)), _ptr(topk_ids), T, topk, epilogue,
                                    _ptr(combine_w), _ptr(out), out_dtype, _ptr(ws), ws_bytes, _stream()))
+    return out
+
+
+def qarl_qgemm_grouped_dx(W, dy, expert_offsets, M, out_row_map=None, out=None, out_dtype=QARL_OUT_BF16):
+    """Input gradient of the grouped W4A16 GEMM (straight-through backward); see include/qarl.h."""
+    if out is None:
+        out = torch.empty((M, W.K), dtype=torch.float32 if out_dtype == QARL_OUT_F32 else torch.bfloat16, device=dy.device)
+    _check(lib().qarl_qgemm_grouped_dx(C.byref(W.desc), _ptr(dy), _ptr(expert_offsets), M, _ptr(out_row_map), _ptr(out),
+                                       out_dtype, _stream()))
+    return out
+
+
+def qarl_grouped_dw(dy, x, expert_offsets, E, row_map=None, out=None, out_dtype=QARL_OUT_BF16):
+    """Weight gradient dy^T x per expert (passed straight to the masters); see include/qarl.h."""
+    M, N = dy.shape
+    K = x.shape[1]
+    if out is None:
+        out = torch.empty((E, N, K), dtype=torch.float32 if out_dtype == QARL_OUT_F32 else torch.bfloat16, device=dy.device)
+    _check(lib().qarl_grouped_dw(_ptr(dy), _ptr(x), _ptr(row_map), _ptr(expert_offsets), M, E, N, K, _ptr(out), out_dtype,
+                                 _stream()))
     return out
 
 

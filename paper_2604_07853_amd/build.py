@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqarl.so")
-SOURCES = ["api.hip", "quantize.hip", "route.hip", "qgemm_stream_fp8.hip", "qgemm_stream_w4.hip", "qgemm_tile.hip",
+SOURCES = ["api.hip", "quantize.hip", "route.hip", "qgemm_stream_fp8.hip", "qgemm_stream_w4.hip", "qgemm_tile.hip", "qgemm_backward.hip",
            "qgemm_tile_fp8.hip", "combine.hip", "logprob.hip", "tbpo.hip"]
 # packed fp32 operations are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

@@ -442,6 +442,76 @@ int qarl_qgemm_routed(const qarl_qweight *W, const void *x, int x_per_token, con
     return QARL_OK;
 }
 
+int qarl_qgemm_grouped_dx(const qarl_qweight *W, const void *dy_bf16, const int32_t *expert_offsets, int64_t M,
+                          const int32_t *out_row_map, void *dx, int out_dtype, void *stream)
+{
+    int rc = check_qweight(W, "qarl_qgemm_grouped_dx");
+    if (rc) return rc;
+    if (W->fmt != QARL_W4A16_G128) {
+        set_error("qarl_qgemm_grouped_dx: W4A16_G128 weights only (got format %d)", W->fmt);
+        return QARL_ERR_UNSUPPORTED;
+    }
+    if (M < 0 || M > 0x7fffffffLL / 2) {
+        set_error("qarl_qgemm_grouped_dx: bad M");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (out_dtype != QARL_OUT_BF16 && out_dtype != QARL_OUT_F32) {
+        set_error("qarl_qgemm_grouped_dx: unknown out_dtype %d", out_dtype);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (M == 0) return QARL_OK;
+    if (!dy_bf16 || !expert_offsets || !dx) {
+        set_error("qarl_qgemm_grouped_dx: null pointer");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!aligned16(dy_bf16) || !aligned16(dx)) {
+        set_error("qarl_qgemm_grouped_dx: dy and dx must be 16-byte aligned");
+        return QARL_ERR_ALIGNMENT;
+    }
+    GemmArgs a;
+    a.fmt = W->fmt;
+    a.E = W->E;
+    a.N = W->N;
+    a.K = W->K;
+    a.codes = W->codes;
+    a.scales = W->scales;
+    a.x = dy_bf16;
+    a.x_scales = nullptr;
+    a.x_group_sums = nullptr;
+    a.row_map = nullptr;
+    a.out_row_map = out_row_map;
+    a.offsets = expert_offsets;
+    a.M = M;
+    a.x_rows = M;
+    a.epilogue = QARL_EPI_NONE;
+    a.out = dx;
+    a.out_f32 = (out_dtype == QARL_OUT_F32);
+    return launch_qgemm_dx(a, (hipStream_t)stream);
+}
+
+int qarl_grouped_dw(const void *dy_bf16, const void *x_bf16, const int32_t *row_map, const int32_t *expert_offsets,
+                    int64_t M, int E, int N, int K, void *dw, int out_dtype, void *stream)
+{
+    if (E <= 0 || N <= 0 || K <= 0 || M < 0) {
+        set_error("qarl_grouped_dw: E, N, K > 0 and M >= 0 required");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (out_dtype != QARL_OUT_BF16 && out_dtype != QARL_OUT_F32) {
+        set_error("qarl_grouped_dw: unknown out_dtype %d", out_dtype);
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!expert_offsets || !dw || (M > 0 && (!dy_bf16 || !x_bf16))) {
+        set_error("qarl_grouped_dw: null pointer");
+        return QARL_ERR_INVALID_ARG;
+    }
+    if (!aligned16(dy_bf16) || !aligned16(x_bf16) || !aligned16(dw)) {
+        set_error("qarl_grouped_dw: dy, x and dw must be 16-byte aligned");
+        return QARL_ERR_ALIGNMENT;
+    }
+    return launch_grouped_dw(dy_bf16, x_bf16, row_map, expert_offsets, E, N, K, dw, out_dtype == QARL_OUT_F32,
+                             (hipStream_t)stream);
+}
+
 int qarl_tbpo_objective(const float *lp_current, const float *lp_old, const float *lp_sampler, int T,
                         const int32_t *seq_offsets, int S, const float *advantage, float eps_low, float eps_high,
                         float delta_low, float delta_high, float tis_cap_c, float *r_seq, float *w_seq_clipped,

@@ -166,6 +166,10 @@ bool qgemm_stream_w4_supported(int N, int K);
 bool qgemm_stream_w4_routed_supported(int N, int K, int T, int topk);
 int launch_qgemm_tile(const GemmArgs &a, hipStream_t s);
 int launch_qgemm_tile_fp8(const GemmArgs &a, hipStream_t s);
+// Straight-through backward of the W4A16 grouped GEMM: a.x = dY bf16 [M][N], a.out = dX [M][K]
+int launch_qgemm_dx(const GemmArgs &a, hipStream_t s);
+int launch_grouped_dw(const void *dy, const void *x, const int32_t *row_map, const int32_t *offsets, int E, int N, int K,
+                      void *out, int out_f32, hipStream_t s);
 int launch_group_sums(const void *x_bf16, int64_t rows, int K, float *sums, hipStream_t s);
 int launch_combine(const float *y_pair_order, const float *w, int T, int topk, int N, void *out, int out_f32,
                    hipStream_t s);

@@ -1,0 +1,149 @@
+"""GPU parity of the straight-through backward of the grouped W4A16 GEMM (section 3.1, item 2) against the oracle:
+dX = dY What (bit-exact on one-hot gradients and in the exact-integer regime) and dW = dY^T X."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_07853_amd import synth
+from gpu_util import np_bits, norm_err, norm_err_bf16
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-3
+TOL_F32 = 2e-5       # dW: bf16 x bf16 products are exact in fp32; accumulation order only
+# dX is a 16-bit backward: the scaled gradient dY * s is rounded to bf16 once before the contraction (as a BF16
+# trainer rounds the dequantized weight).  Each of the N terms is off by up to half a bf16 ulp, between 2^-9 and 2^-8
+# of its size depending on where it lies in its binade (rms about 1.7e-3 of the term), independently, so the sum is
+# off by about 1.7e-3 of its rms whatever N is; over 10^5 .. 10^7 outputs the largest deviation is 4 to 5 times
+# that.  One-hot gradients and the exact-integer regime are exact (tests above).
+TOL_DX_F32 = 1e-2
+TOL_DX_RMS = 2.5e-3  # the rms itself
+
+
+@pytest.fixture(scope="module")
+def q():
+    from paper_2604_07853_amd import binding
+    binding.lib()
+    return binding
+
+
+def _i32(a):
+    return torch.tensor(np.asarray(a), dtype=torch.int32, device="cuda")
+
+
+def test_one_hot_gradient_bit_exact(q, oracle):
+    E, N, K = 2, 128, 256
+    w = synth.normal_bf16((E, N, K), 0.02, seed=81)
+    codes, scales = oracle.quantize_int4(np_bits(w))
+    deq = oracle.dequant_int4(codes, scales)
+    qw = q.qarl_quantize_weights(w.cuda())
+    eye = torch.eye(N).to(torch.bfloat16)
+    dy = torch.cat([eye, eye]).cuda()
+    dx = q.qarl_qgemm_grouped_dx(qw, dy, _i32([0, N, 2 * N]), 2 * N, out_dtype=q.QARL_OUT_F32).cpu().numpy()
+    assert np.array_equal(dx[:N], deq[0]) and np.array_equal(dx[N:], deq[1])
+
+
+def test_exact_integer_regime_bit_exact(q, oracle):
+    rng = np.random.default_rng(82)
+    E, N, K, rows = 3, 128, 256, (40, 0, 75)
+    M = sum(rows)
+    qi = rng.integers(-7, 8, size=(E, N, K))
+    qi[:, :, ::128] = 7
+    ex = rng.integers(-3, 2, size=(E, N, K // 128))
+    w = torch.tensor(qi * np.repeat(2.0 ** ex, 128, axis=2), dtype=torch.float32).to(torch.bfloat16)
+    dy = torch.tensor(rng.integers(-4, 5, size=(M, N)), dtype=torch.float32).to(torch.bfloat16)
+    x = torch.tensor(rng.integers(-4, 5, size=(M, K)), dtype=torch.float32).to(torch.bfloat16)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    rm = rng.permutation(M).astype(np.int32)
+    codes, scales = oracle.quantize_int4(np_bits(w))
+    qw = q.qarl_quantize_weights(w.cuda())
+    dx = q.qarl_qgemm_grouped_dx(qw, dy.cuda(), _i32(off), M, out_dtype=q.QARL_OUT_F32)
+    assert np.array_equal(dx.cpu().numpy().astype(np.float64), oracle.qgemm_w4a16_dx(np_bits(dy), codes, scales, off))
+    dw = q.qarl_grouped_dw(dy.cuda(), x.cuda(), _i32(off), E, row_map=_i32(rm), out_dtype=q.QARL_OUT_F32)
+    assert np.array_equal(dw.cpu().numpy().astype(np.float64), oracle.grouped_dw(np_bits(dy), np_bits(x), off, E, rm))
+    assert bool((dw[1] == 0).all())                                  # the expert without rows gets zeros
+
+
+@pytest.mark.parametrize("E,N,K,rows", [(3, 256, 384, (37, 0, 300)), (2, 128, 128, (1, 129)), (4, 384, 1024, (128, 256, 5, 64))])
+def test_general_data_both_gradients(q, oracle, E, N, K, rows):
+    seed = 8300 + N + K
+    rng = np.random.default_rng(seed)
+    M = int(sum(rows))
+    w = synth.normal_bf16((E, N, K), 0.02, seed=seed)
+    dy = synth.normal_bf16((M, N), 1.0, seed=seed + 1)
+    x = synth.normal_bf16((M + 7, K), 1.0, seed=seed + 2)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    rm = rng.permutation(M + 7)[:M].astype(np.int32)
+    scatter = rng.permutation(M).astype(np.int32)
+    codes, scales = oracle.quantize_int4(np_bits(w))
+    qw = q.qarl_quantize_weights(w.cuda())
+    dx_ref = oracle.qgemm_w4a16_dx(np_bits(dy), codes, scales, off)
+    dx = q.qarl_qgemm_grouped_dx(qw, dy.cuda(), _i32(off), M, out_dtype=q.QARL_OUT_F32)
+    assert norm_err(dx.cpu().numpy(), dx_ref) <= TOL_DX_F32
+    assert np.sqrt(((dx.cpu().numpy() - dx_ref) ** 2).mean() / (dx_ref ** 2).mean()) <= TOL_DX_RMS
+    dxb = torch.full((M, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    q.qarl_qgemm_grouped_dx(qw, dy.cuda(), _i32(off), M, out_row_map=_i32(scatter), out=dxb)
+    want = np.empty_like(dx_ref)
+    want[scatter] = dx_ref                                           # row i of the problem lands in row scatter[i]
+    assert norm_err(dxb.float().cpu().numpy(), want) <= TOL_DX_F32 + 2.0 ** -8     # plus the output's own rounding
+    dw_ref = oracle.grouped_dw(np_bits(dy), np_bits(x), off, E, rm)
+    dw = q.qarl_grouped_dw(dy.cuda(), x.cuda(), _i32(off), E, row_map=_i32(rm), out_dtype=q.QARL_OUT_F32)
+    assert norm_err(dw.cpu().numpy(), dw_ref) <= TOL_F32
+    dwb = q.qarl_grouped_dw(dy.cuda(), x.cuda(), _i32(off), E, row_map=_i32(rm))
+    assert norm_err_bf16(dwb.float().cpu().numpy(), dw_ref) <= TOL_BF16
+    # the adjoint identity on the GPU's own results: <dY, Y> = <dX, X> = <dW, What>
+    y = q.qarl_qgemm_grouped(qw, x.cuda(), _i32(off), M, row_map=_i32(rm), out_dtype=q.QARL_OUT_F32).double()
+    a = float((dy.cuda().double() * y).sum())
+    b = float((dx.double() * x.cuda().double()[torch.tensor(rm, dtype=torch.long, device="cuda")]).sum())
+    c = float((dw.double() * torch.tensor(oracle.dequant_int4(codes, scales), device="cuda").double()).sum())
+    scale = float(dy.double().norm() * y.norm().cpu())
+    assert abs(a - b) <= 2e-3 * scale and abs(a - c) <= 1e-4 * scale
+
+
+def test_backward_full_size_gate_up_sampled(q, oracle):
+    """The gate_up matrices of the full layer (128 experts, N = 1536, K = 2048) at 2048 tokens with a Zipf router:
+    dX on sampled rows, dW on the most and least loaded expert and one in between."""
+    E, H, I, TOPK = synth.E, synth.H, synth.I, synth.TOPK
+    N, K, T = 2 * I, H, 2048
+    gu, _ = synth.expert_weights(E, H, I, seed=8400, device="cuda")
+    qw = q.qarl_quantize_weights(gu)
+    codes, scales = oracle.quantize_int4(np_bits(gu))
+    del gu
+    lg = synth.router_logits(T, E, seed=8401, device="cuda", zipf_s=1.1)
+    r = q.qarl_moe_route(lg, TOPK)
+    M = T * TOPK
+    off = r.offsets.cpu().numpy()
+    tok = r.tokens.cpu().numpy()
+    x = synth.normal_bf16((T, K), 1.0, seed=8402, device="cuda")
+    dy = synth.normal_bf16((M, N), 1.0, seed=8403, device="cuda")
+    dx = q.qarl_qgemm_grouped_dx(qw, dy, r.offsets, M, out_dtype=q.QARL_OUT_F32)
+    dw = q.qarl_grouped_dw(dy, x, r.offsets, E, row_map=r.tokens, out_dtype=q.QARL_OUT_F32)
+    counts = np.diff(off)
+    rng = np.random.default_rng(8404)
+    rows = np.unique(np.concatenate([off[:-1][counts > 0], off[1:][counts > 0] - 1, rng.integers(0, M, 48)]))
+    # the oracle on the sampled rows only: one sub-problem whose offsets count the sampled rows per expert
+    exp_of = np.searchsorted(off, rows, side="right") - 1
+    sub = np.concatenate([[0], np.cumsum(np.bincount(exp_of, minlength=E))]).astype(np.int32)
+    dx_ref = oracle.qgemm_w4a16_dx(np_bits(dy)[rows], codes, scales, sub)
+    assert norm_err(dx[torch.from_numpy(rows).cuda()].cpu().numpy(), dx_ref) <= TOL_DX_F32
+    order = np.argsort(counts)
+    for e in (int(order[-1]), int(order[0]), int(order[E // 2])):
+        lo, hi = off[e], off[e + 1]
+        ref = oracle.grouped_dw(np_bits(dy)[lo:hi], np_bits(x), np.array([0, hi - lo], dtype=np.int32), 1, tok[lo:hi])
+        assert norm_err(dw[e].cpu().numpy(), ref[0]) <= TOL_F32, e
+
+
+def test_backward_errors(q):
+    w = synth.normal_bf16((1, 64, 128), 0.02, seed=85).cuda()
+    qw = q.qarl_quantize_weights(w)                                  # N = 64: not a multiple of 128
+    dy = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(q.QarlError) as ei:
+        q.qarl_qgemm_grouped_dx(qw, dy, _i32([0, 4]), 4)
+    assert ei.value.status == q.QARL_ERR_UNSUPPORTED
+    q8 = q.qarl_quantize_weights(synth.normal_bf16((1, 128, 128), 0.02, seed=86).cuda(), q.QARL_FP8_E4M3_CH)
+    with pytest.raises(q.QarlError) as ei:
+        q.qarl_qgemm_grouped_dx(q8, torch.zeros((4, 128), dtype=torch.bfloat16, device="cuda"), _i32([0, 4]), 4)
+    assert ei.value.status == q.QARL_ERR_UNSUPPORTED
+    with pytest.raises(q.QarlError) as ei:
+        q.qarl_grouped_dw(dy, torch.zeros((4, 128), dtype=torch.bfloat16, device="cuda"), _i32([0, 4]), 1)
+    assert ei.value.status == q.QARL_ERR_UNSUPPORTED
