@@ -156,7 +156,8 @@ int qarl_moe_route(const void *logits_bf16, int T, int E, int topk, int renorm, 
  *                        written by qarl_moe_route
  *   out_dtype  QARL_OUT_BF16 or QARL_OUT_F32 (SILU_MUL: bf16 only)
  *   path       AUTO picks DECODE when the mean rows per expert is small and the shape fits it
- *              (DECODE keeps whole rows of x in LDS: W4A16 needs K % 256 == 0 and K <= 2048)
+ *              (DECODE keeps whole rows of x in LDS: W4A16 needs K % 256 == 0 and K <= 4096, with 16-row
+ *              instead of 32-row blocks beyond 2048)
  * Errors: INVALID_ARG, ALIGNMENT, UNSUPPORTED (shape outside the kernels' domain),
  * WORKSPACE (ws missing or smaller than the call needs).  M == 0 is a no-op. */
 int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scales, int64_t x_rows,

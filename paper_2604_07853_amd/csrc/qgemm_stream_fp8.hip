@@ -347,7 +347,7 @@ bool qgemm_stream_supported(int fmt, int N, int K)
 int launch_qgemm_stream(const GemmArgs &a, hipStream_t s)
 {
     if (!qgemm_stream_supported(a.fmt, a.N, a.K)) {
-        set_error("qgemm (decode path): unsupported shape N=%d K=%d (needs N %% 32 == 0; W4A16: K %% 256 == 0, K <= 2048; "
+        set_error("qgemm (decode path): unsupported shape N=%d K=%d (needs N %% 32 == 0; W4A16: K %% 256 == 0, K <= 4096; "
                   "FP8: K %% 128 == 0, K <= 4096; the token tile of one row block must fit LDS)", a.N, a.K);
         return QARL_ERR_UNSUPPORTED;
     }

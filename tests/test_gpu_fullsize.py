@@ -319,9 +319,10 @@ def test_logprob_config3_and_path_mismatch(q, oracle, layer_int4):
 
 def test_dense_mlp_second_model_shape(q, oracle):
     """A dense (non-MoE) SiLU-gated MLP of a second model shape through the same entry points: hidden 4096,
-    intermediate 12288 (E = 1), 4096 tokens.  K = 4096 is beyond the decode kernel's whole-row LDS tile, so the
-    decode path must refuse it and AUTO must take the MFMA-tiled path.  Codes and scales in full, GEMM outputs on
-    sampled rows (first and last, rows around the 64-row tile borders, a seeded draw)."""
+    intermediate 12288 (E = 1), 4096 tokens on the MFMA-tiled path (AUTO), and a 40-token decode batch of the
+    gate_up projection on the weight-streaming path, whose K = 4096 takes the 16-row LDS tile (three row blocks).
+    K = 12288 (the down projection) is beyond that kernel and must be refused there.  Codes and scales in full,
+    GEMM outputs on sampled rows (first and last, rows around the 64-row tile borders, a seeded draw)."""
     H2, I2, T = 4096, 12288, 4096
     gu = synth.normal_bf16((1, 2 * I2, H2), 0.02, seed=700, device="cuda")
     dn = synth.normal_bf16((1, H2, I2), 0.02, seed=701, device="cuda")
@@ -334,10 +335,22 @@ def test_dense_mlp_second_model_shape(q, oracle):
         assert np.array_equal(unblock_int4(qw.codes, 1, N, K), c)
         assert np.array_equal(np_bits(qw.scales).reshape(s.shape), s)
     off = torch.tensor([0, T], dtype=torch.int32, device="cuda")
-    with pytest.raises(q.QarlError) as ei:
-        q.qarl_qgemm_grouped(qgu, x, off, T, epilogue=q.QARL_EPI_SILU_MUL, path=q.QARL_PATH_DECODE)
-    assert ei.value.status == q.QARL_ERR_UNSUPPORTED
     a = q.qarl_qgemm_grouped(qgu, x, off, T, epilogue=q.QARL_EPI_SILU_MUL, path=q.QARL_PATH_AUTO)
+    with pytest.raises(q.QarlError) as ei:
+        q.qarl_qgemm_grouped(qdn, a, off, T, out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_DECODE)
+    assert ei.value.status == q.QARL_ERR_UNSUPPORTED
+    # decode batch through the streaming kernel: SiLU epilogue in bf16 and the plain one in fp32
+    Td = 40
+    offd = torch.tensor([0, Td], dtype=torch.int32, device="cuda")
+    xd = x[:Td].contiguous()
+    subd = np.array([0, Td], dtype=np.int32)
+    gud_ref = oracle.qgemm_w4a16(np_bits(xd), guc, gus, subd)
+    yd = q.qarl_qgemm_grouped(qgu, xd, offd, Td, out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_DECODE)
+    assert norm_err(yd.cpu().numpy(), gud_ref) <= TOL_F32
+    ad = q.qarl_qgemm_grouped(qgu, xd, offd, Td, epilogue=q.QARL_EPI_SILU_MUL, path=q.QARL_PATH_DECODE)
+    ad_ref_bits, ad_ref = oracle.silu_mul(gud_ref)
+    assert norm_err_bf16(ad.float().cpu().numpy(), ad_ref) <= TOL_BF16
+    assert flip_fraction(np_bits(ad), ad_ref_bits) <= MAX_FLIPS
     y = q.qarl_qgemm_grouped(qdn, a, off, T, out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_AUTO)
     rng = np.random.default_rng(703)
     rows = np.unique(np.concatenate([[0, 1, 63, 64, 65, 127, 128, T - 65, T - 64, T - 1], rng.integers(0, T, 22)]))

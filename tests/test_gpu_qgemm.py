@@ -66,7 +66,7 @@ def test_dense_w4a16_config1(q, oracle):
         assert fl <= MAX_FLIPS, (path, fl)
 
 
-@pytest.mark.parametrize("K,N", [(256, 64), (768, 32)])
+@pytest.mark.parametrize("K,N", [(256, 64), (768, 32), (4096, 32)])
 def test_one_hot_probe_bit_exact_both_paths(q, oracle, K, N):
     """x = rows of the identity: the output is the dequantized weight s*q itself; both paths
     must reproduce it exactly (identical dequantized numerics)."""
@@ -323,6 +323,7 @@ def test_ragged_shapes_both_paths(q, oracle, fmt, E, N, K, rows):
 
 
 @pytest.mark.parametrize("E,N,K,T,topk", [(8, 64, 2048, 600, 3),     # row maps too large to sit beside the LDS tile
+                                          (3, 96, 4096, 50, 2),      # K beyond 2048: 16-row LDS tile, several row blocks
                                           (4, 64, 512, 37, 3),       # M = 111: last quad of the map is partial
                                           (16, 32, 256, 1500, 3),    # M = 4500: maps stay in global memory
                                           (6, 96, 768, 171, 5)])     # 64-row blocks (K fits), M = 855
