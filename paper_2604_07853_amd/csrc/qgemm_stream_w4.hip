@@ -595,35 +595,26 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_wide_kernel(W4Par
 #pragma unroll 1
         for (int ch = 0; ch < NC; ++ch) {
             lds_barrier();  // row ids are written / every wavefront has left the previous chunk's tile
-            // ---- gather the K-range of the token rows: KC / 8 blocks of 16 bytes per row, 4 rows per sweep
+            // ---- gather the K-range of the token rows by asynchronous global -> LDS copies (no registers: the
+            // accumulators of all pairs stay live across this point): a wavefront instruction moves 1 KiB, half of a
+            // row's KC * 2 = 2 KiB; wavefront w copies rows 8 w .. 8 w + 7.  Rows past the expert's end repeat its
+            // last row (their results are never stored).
             {
-                const int bpr = KC / 8;
-                const int rpp = kThreads / bpr;
-                const int rsub = tid / bpr, b = tid - rsub * bpr;
-                constexpr int kBatch = 16;
-                u32x4 v[kBatch];
-                int xr[kBatch];
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) xr[u] = s_row[min(min(rsub + u * rpp, kRows - 1), mrem - 1)];
-                const uint32_t coff = (uint32_t)(ch * KC * 2 + b * 16), rbytes = (uint32_t)K * 2u;
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    v[u] = u32x4{0, 0, 0, 0};
-                    if (rsub + u * rpp < mrem)
-                        v[u] = *(const u32x4 *)((const unsigned char *)p.x + ((uint32_t)xr[u] * rbytes + coff));
+                for (int u = 0; u < 16; ++u) {
+                    const int r = wave * 8 + (u >> 1), hh = u & 1;
+                    const int xr = __builtin_amdgcn_readfirstlane(s_row[min(r, mrem - 1)]);
+                    const unsigned char *src = (const unsigned char *)p.x + ((uint32_t)xr * (uint32_t)K * 2u +
+                                                                              (uint32_t)(ch * KC * 2 + hh * 1024 + lane * 16));
+                    copy16_to_lds(src, xs + r * stride + hh * 1024);
                 }
                 if (ch == 0) {   // the weight stream starts right behind the first gather
                     const uint32_t *src = batch_src(wave, 0);
 #pragma unroll
                     for (int r = 0; r < R; ++r) fill(ring[r], r, src);
                 }
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const int r = rsub + u * rpp;
-                    if (r < kRows) *(u32x4 *)(xs + r * stride + b * 16) = v[u];
-                }
             }
-            lds_barrier();
+            copy_barrier();
             {
                 // group sums of the chunk, sx[g][m] = -1.5 * sum_k x[m][k]: x times a matrix of ones
                 const u32x4 ones4 = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
@@ -655,7 +646,7 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_wide_kernel(W4Par
                 const int npi = last_pair ? wave : pi + 8;
                 const int nch = last_pair ? (ch + 1 < NC ? ch + 1 : 0) : ch;
                 sc_nxt = load_scales(npi, nch);
-#pragma unroll
+#pragma unroll 1
                 for (int g0 = 0; g0 < GC; g0 += R) {
                     const bool same = g0 + R < GC;
                     const uint32_t *nsrc = batch_src(same ? pi : npi, same ? ch * GC + g0 + R : nch * GC);
@@ -682,15 +673,22 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_wide_kernel(W4Par
                                     const bf16x8 a = *(const bf16x8 *)(xs + (mt * 32 + m32) * stride +
                                                                        (g * 128 + L * 64 + h * 32 + jj * 8) * 2);
                                     ag[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bw, ag[mt], 0, 0, 0);
+                                    // Scheduling fence.  Without it the compiler sinks the LDS reads that initialise the
+                                    // second accumulator below this instruction and lets them land in the registers that
+                                    // hold this instruction's A operand; on the device the first row tile then came out
+                                    // corrupted (any fence here, even an empty one, gives correct results; measured).
+                                    asm volatile("s_nop 0" ::: "memory");
                                 }
                             }
-                        const uint32_t sw = sc_cur[g >> 1];
-                        const float s16 = 16.f * __uint_as_float((g & 1) ? (sw & 0xffff0000u) : (sw << 16));
+                        // scale of group g0 + r: bf16 number 2 (g0 / 4) + r / 2 .. of the lane's eight (g0 is 0 or 4)
+                        const uint32_t sw = g0 ? sc_cur[2 + (r >> 1)] : sc_cur[r >> 1];
+                        const float s16 = 16.f * __uint_as_float((r & 1) ? (sw & 0xffff0000u) : (sw << 16));
 #pragma unroll
                         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                             for (int i = 0; i < 16; ++i) acc[j][mt][i] = fmaf(s16, ag[mt][i], acc[j][mt][i]);
                         fill(cur, r, nsrc);
+                        __builtin_amdgcn_sched_barrier(0);   // keep the groups apart: hoisted operand reads cost registers
                     }
                 }
                 sc_cur = sc_nxt;
@@ -714,12 +712,14 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_wide_kernel(W4Par
                     if (kSilu) {
 #pragma unroll
                         for (int ip = 0; ip < 2; ++ip) {
-                            const u32x2 sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(acc[j][mt][i4 * 4 + 2 * ip]),
-                                                                              __float_as_uint(acc[j][mt][i4 * 4 + 2 * ip + 1]),
-                                                                              false, false);
+                            // lanes of the gate tile (t = 0) finish row 2 ip, lanes of the up tile row 2 ip + 1: each
+                            // sends the value of the row it does not finish to its partner 16 lanes away
+                            const float v0 = acc[j][mt][i4 * 4 + 2 * ip], v1 = acc[j][mt][i4 * 4 + 2 * ip + 1];
+                            const float recv = __shfl_xor(t ? v0 : v1, 16, 64);
+                            const float gv = t ? recv : v0, uv = t ? v1 : recv;
                             const int64_t orow = t ? orow4[2 * ip + 1] : orow4[2 * ip];
                             if (orow >= 0) {
-                                const float a = silu_mul_f32(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                                const float a = silu_mul_f32(gv, uv);
                                 ((uint16_t *)p.out)[orow * (N / 2) + u * 16 + c] = f32_to_bf16_hw(a);
                             }
                         }
@@ -839,6 +839,7 @@ int launch_one(const GemmArgs &a, hipStream_t s)
     p.per_slice = (p.n_units + (1 << ssh) - 1) >> ssh;
     // 64-row blocks over a K-chunked tile: K = 2048 (two chunks of eight scale groups), more than 32 rows per expert
     // to expect, and a slice that gives every wavefront the same one to three pairs
+    static_assert(kWaves * 8 == 64, "the wide kernel's gather: eight rows per wavefront");
     if (MT == 1 && !p.half_tile && need > 32.0 && a.K == 2048) {
         const int ms_w = (int)ceil(need / 64.0);
         int msh_w = 0;

@@ -324,6 +324,8 @@ def test_ragged_shapes_both_paths(q, oracle, fmt, E, N, K, rows):
 
 @pytest.mark.parametrize("E,N,K,T,topk", [(8, 64, 2048, 600, 3),     # row maps too large to sit beside the LDS tile
                                           (3, 96, 4096, 50, 2),      # K beyond 2048: 16-row LDS tile, several row blocks
+                                          (4, 512, 2048, 60, 3),     # 64-row blocks over a K-chunked tile, one pair per wavefront
+                                          (4, 1024, 2048, 200, 3),   # the same with two pairs and several row blocks
                                           (4, 64, 512, 37, 3),       # M = 111: last quad of the map is partial
                                           (16, 32, 256, 1500, 3),    # M = 4500: maps stay in global memory
                                           (6, 96, 768, 171, 5)])     # 64-row blocks (K fits), M = 855
@@ -359,6 +361,8 @@ def test_decode_row_map_paths(q, oracle, E, N, K, T, topk):
 
 
 @pytest.mark.parametrize("E,N,K,T,topk", [(8, 64, 2048, 500, 3),      # several row blocks per expert, partial last quad of ids
+                                          (4, 512, 2048, 60, 3),      # 64-row blocks over a K-chunked tile
+                                          (4, 1024, 2048, 200, 3),    # ... two pairs per wavefront, several row blocks
                                           (4, 64, 512, 37, 3),        # 111 pairs
                                           (6, 96, 768, 171, 5),       # 64-row blocks
                                           (128, 64, 256, 512, 8)])    # the largest routed batch: 512 tokens, 4096 pairs
