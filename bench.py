@@ -359,12 +359,19 @@ def main():
                 l8 = q.MoELayer(qgu8, qdn8, T8, TOPK, path, dev)
                 ms8 = timed(lambda: l8.forward(x8, lg8), 20, 3)
                 r8, M8 = l8.routing, T8 * TOPK
-                ms8_gu = timed(lambda: q.qarl_qgemm_grouped(qgu8, l8.xq, r8.offsets, M8, row_map=r8.tokens, x_scales=l8.sx,
-                                                            epilogue=q.QARL_EPI_SILU_MUL, out=l8.a, path=path,
-                                                            ws=l8.ws), 20, 3)
-                y8 = torch.empty((M8, H), dtype=torch.float32, device=dev)
-                ms8_dn = timed(lambda: q.qarl_qgemm_grouped(qdn8, l8.aq, r8.offsets, M8, x_scales=l8.sa, out=y8,
-                                                            out_dtype=q.QARL_OUT_F32, path=path, ws=l8.ws), 20, 3)
+                if l8.routed:   # decode: the GEMMs read the router's ids and quantize the rows they gather
+                    ms8_gu = timed(lambda: q.qarl_qgemm_routed(qgu8, x8, r8.ids, T8, TOPK, True, epilogue=q.QARL_EPI_SILU_MUL,
+                                                               out=l8.a, ws=l8.ws), 20, 3)
+                    y8 = torch.empty((M8, H), dtype=torch.float32, device=dev)
+                    ms8_dn = timed(lambda: q.qarl_qgemm_routed(qdn8, l8.a, r8.ids, T8, TOPK, False, out=y8,
+                                                               out_dtype=q.QARL_OUT_F32, ws=l8.ws), 20, 3)
+                else:
+                    ms8_gu = timed(lambda: q.qarl_qgemm_grouped(qgu8, l8.xq, r8.offsets, M8, row_map=r8.tokens, x_scales=l8.sx,
+                                                                epilogue=q.QARL_EPI_SILU_MUL, out=l8.a, path=path,
+                                                                ws=l8.ws), 20, 3)
+                    y8 = torch.empty((M8, H), dtype=torch.float32, device=dev)
+                    ms8_dn = timed(lambda: q.qarl_qgemm_grouped(qdn8, l8.aq, r8.offsets, M8, x_scales=l8.sa, out=y8,
+                                                                out_dtype=q.QARL_OUT_F32, path=path, ws=l8.ws), 20, 3)
                 del y8
                 f8 = synth.flops_moe(T8)
                 extra["%s_%s_%dtok" % (fname, tag, T8)] = {

@@ -17,6 +17,7 @@ QARL_OK = 0
 QARL_ERR_INVALID_ARG, QARL_ERR_UNSUPPORTED, QARL_ERR_ALIGNMENT, QARL_ERR_WORKSPACE, QARL_ERR_HIP = -1, -2, -3, -4, -5
 QARL_W4A16_G128, QARL_FP8_E4M3_CH, QARL_FP4_E2M1_CH, QARL_W4A8_G128 = 1, 2, 3, 4
 INT4_FORMATS = (QARL_W4A16_G128, QARL_W4A8_G128)          # int4 g128 codes + bf16 group scales
+ROUTED_FORMATS = (QARL_W4A16_G128, QARL_FP8_E4M3_CH, QARL_FP4_E2M1_CH)
 E4M3_ACT_FORMATS = (QARL_FP8_E4M3_CH, QARL_FP4_E2M1_CH, QARL_W4A8_G128)   # e4m3 activations + row scales
 QARL_PATH_AUTO, QARL_PATH_DECODE, QARL_PATH_PREFILL = 0, 1, 2
 QARL_EPI_NONE, QARL_EPI_SILU_MUL, QARL_EPI_COMBINE = 0, 1, 2
@@ -316,9 +317,10 @@ class MoELayer:
     def __init__(self, gate_up: QWeight, down: QWeight, T, topk=8, path=QARL_PATH_AUTO, device="cuda", routed=None):
         self.gu, self.dn, self.T, self.topk, self.path = gate_up, down, T, topk, path
         self.fp8 = gate_up.fmt in E4M3_ACT_FORMATS        # e4m3 activations with per-row scales
-        # decode-sized W4A16 batches skip the grouping pass: the GEMMs read the router's ids themselves
+        # decode-sized batches skip the grouping pass: the GEMMs read the router's ids themselves (and, for the
+        # e4m3-activation formats, quantize the 16-bit token rows they gather)
         self.routed = (routed if routed is not None else
-                       (gate_up.fmt == QARL_W4A16_G128 and path == QARL_PATH_DECODE and 0 < T <= 512 and T * topk <= 4096))
+                       (gate_up.fmt in ROUTED_FORMATS and path == QARL_PATH_DECODE and 0 < T <= 512 and T * topk <= 4096))
         E, I, H = gate_up.E, gate_up.N // 2, gate_up.K
         self.E, self.I, self.H = E, I, H
         M = T * topk
@@ -329,7 +331,7 @@ class MoELayer:
         need = max(qarl_qgemm_workspace_bytes(gate_up, T, M, QARL_EPI_SILU_MUL),
                    qarl_qgemm_workspace_bytes(down, M, M, QARL_EPI_COMBINE), 16)
         self.ws = torch.empty((need,), dtype=torch.uint8, device=device)
-        if self.fp8:
+        if self.fp8 and not self.routed:
             self.xq = torch.empty((T, H), dtype=torch.uint8, device=device)
             self.sx = torch.empty((T,), dtype=torch.float32, device=device)
             self.aq = torch.empty((M, I), dtype=torch.uint8, device=device)

@@ -98,22 +98,16 @@ static size_t ws_sums_bytes(const qarl_qweight *W, int64_t x_rows)
     return int4_weights(W->fmt) ? align256((size_t)x_rows * (size_t)(W->K / 128) * sizeof(float)) : 0;
 }
 
-// Format bridges: W4A8 widens the e4m3 activations to bf16 (exact) for the W4A16 kernels; the tiled path of FP4
-// widens the e2m1 weights to e4m3 bytes (exact) for the FP8 kernel.
+// Format bridge: W4A8 widens the e4m3 activations to bf16 (exact) for the W4A16 kernels.
 static size_t ws_xwide_bytes(const qarl_qweight *W, int64_t x_rows)
 {
     return W->fmt == QARL_W4A8_G128 ? align256((size_t)x_rows * (size_t)W->K * 2) : 0;
 }
 
-static size_t ws_wwide_bytes(const qarl_qweight *W)
-{
-    return W->fmt == QARL_FP4_E2M1_CH ? align256((size_t)W->E * (size_t)W->N * (size_t)W->K) : 0;
-}
-
 size_t qarl_qgemm_workspace_bytes(const qarl_qweight *W, int64_t x_rows, int64_t M, int epilogue)
 {
     if (!W || M <= 0 || x_rows <= 0 || W->N <= 0 || W->K <= 0) return 0;
-    return ws_stage_bytes(W, M, epilogue) + ws_sums_bytes(W, x_rows) + ws_xwide_bytes(W, x_rows) + ws_wwide_bytes(W);
+    return ws_stage_bytes(W, M, epilogue) + ws_sums_bytes(W, x_rows) + ws_xwide_bytes(W, x_rows);
 }
 
 size_t qarl_logprob_workspace_bytes(int T, int H, int V)
@@ -316,8 +310,7 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
     const size_t stage = ws_stage_bytes(W, M, epilogue);
     const size_t sums = (use == QARL_PATH_PREFILL) ? ws_sums_bytes(W, x_rows) : 0;
     const size_t xwide = ws_xwide_bytes(W, x_rows);
-    const size_t wwide = (use == QARL_PATH_PREFILL) ? ws_wwide_bytes(W) : 0;
-    const size_t need = stage + sums + xwide + wwide;
+    const size_t need = stage + sums + xwide;
     if (need > 0 && (!ws || ws_bytes < need || !aligned16(ws))) {
         set_error("qarl_qgemm_grouped: this call needs %zu bytes of 16-byte aligned workspace (got %zu)", need, ws_bytes);
         return QARL_ERR_WORKSPACE;
@@ -327,13 +320,6 @@ int qarl_qgemm_grouped(const qarl_qweight *W, const void *x, const float *x_scal
         rc = launch_e4m3_to_bf16(x, x_rows * (int64_t)W->K, x16, st);
         if (rc) return rc;
         a.x = x16;
-    }
-    if (wwide) {   // FP4 on the tiled path: e2m1 codes -> e4m3 bytes, then the FP8 kernel
-        void *c8 = (char *)ws + stage + sums + xwide;
-        rc = launch_widen_e2m1(W->codes, (int64_t)W->E * W->N * W->K, c8, st);
-        if (rc) return rc;
-        a.codes = c8;
-        a.fmt = QARL_FP8_E4M3_CH;
     }
     if (epilogue == QARL_EPI_COMBINE) {
         if (!combine_w || !sorted_pairs) {
@@ -385,9 +371,10 @@ int qarl_qgemm_routed(const qarl_qweight *W, const void *x, int x_per_token, con
         return QARL_ERR_UNSUPPORTED;
     }
     if (T == 0) return QARL_OK;
-    if (W->fmt != QARL_W4A16_G128 || !qgemm_stream_w4_routed_supported(W->N, W->K, T, topk)) {
-        set_error("qarl_qgemm_routed: supports W4A16 in the DECODE path's shapes (N %% 32 == 0, K %% 256 == 0, K <= 2048), "
-                  "T <= 512 and T * topk <= 4096 (got fmt=%d N=%d K=%d T=%d topk=%d)", W->fmt, W->N, W->K, T, topk);
+    if (!qgemm_stream_routed_supported(W->fmt, W->N, W->K, T, topk)) {
+        set_error("qarl_qgemm_routed: supports W4A16 (N %% 32 == 0, K %% 256 == 0, K <= 2048), FP8 and FP4 (N %% 32 == 0, "
+                  "K %% 128 == 0, K <= 4096) with T <= 512 and T * topk <= 4096 (got fmt=%d N=%d K=%d T=%d topk=%d)",
+                  W->fmt, W->N, W->K, T, topk);
         return QARL_ERR_UNSUPPORTED;
     }
     if (!x || !topk_ids || !out) {
@@ -435,7 +422,7 @@ int qarl_qgemm_routed(const qarl_qweight *W, const void *x, int x_per_token, con
         a.out = ws;
         a.out_f32 = 1;
     }
-    rc = launch_qgemm_stream_w4(a, st);
+    rc = launch_qgemm_stream(a, st);
     if (rc) return rc;
     if (epilogue == QARL_EPI_COMBINE)
         return launch_combine((const float *)ws, combine_w, T, topk, W->N, out, out_dtype == QARL_OUT_F32, st);

@@ -59,6 +59,64 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// ---- FP quantizer of section 2.2 along a row, e4m3 flavour (alpha = 448), shared by the row quantizer and by the
+// decode GEMM that quantizes its token rows while it gathers them, so that both produce the same bytes.
+// x / s, correctly rounded, without a divide per element: with y = RN(1 / s) (one IEEE divide per row),
+// q0 = RN(x y) and the exact remainder r = x - q0 s from one FMA, RN(q0 + r y) is the correctly rounded
+// quotient (Markstein's correction step; it needs the correctly rounded reciprocal and no underflow on the
+// way, hence the guard on s; below 2^-11 a quotient may differ from the IEEE one, where every value rounds
+// to an e4m3 zero; the sign is copied from x, as s > 0).  Checked against the IEEE divide for all 65536 bf16
+// values of x and 2^20 scales (the quantizer's own absmax / alpha and random ones): no difference at |x / s| >= 2^-11.
+struct RowScale {
+    float s, y;
+    bool fast;
+    __device__ __forceinline__ explicit RowScale(float s_) : s(s_), y(1.0f / s_)
+    {
+        fast = s_ >= 0x1p-100f && s_ < 0x1p100f && (__float_as_uint(s_) & 0x7fffffu) != 0x7fffffu;
+    }
+    __device__ __forceinline__ float div(float x) const
+    {
+        if (!fast) return x / s;
+        const float q0 = x * y;
+        return copysignf(fmaf(fmaf(-q0, s, x), y, q0), x);   // the sign of x also where the steps end in +0 (x = -0)
+    }
+};
+
+// absmax of eight bf16 values held in four dwords, folded into am
+__device__ __forceinline__ float absmax_bf16x8(u32x4 v, float am)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        am = fmaxf(am, fabsf(__uint_as_float(v[i] << 16)));
+        am = fmaxf(am, fabsf(__uint_as_float(v[i] & 0xffff0000u)));
+    }
+    return am;
+}
+
+// Eight bf16 values -> eight e4m3 bytes of x / s (zeros for a zero row).  v_cvt_pk_fp8_f32 rounds to nearest even
+// into OCP e4m3 (subnormals included) for every finite |t| <= 448 (checked over all 2^32 bit patterns on gfx950
+// against a software encoder); the clamp keeps the quotient of the row's absmax, which may exceed 448 by an ulp,
+// in that range (and sends a NaN to -448).
+__device__ __forceinline__ u32x2 e4m3_quantize_bf16x8(const RowScale &rs, u32x4 v)
+{
+    u32x2 o = {0, 0};
+    if (rs.s != 0.f) {
+        float t[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            t[2 * i] = __builtin_amdgcn_fmed3f(rs.div(__uint_as_float(v[i] << 16)), -448.f, 448.f);
+            t[2 * i + 1] = __builtin_amdgcn_fmed3f(rs.div(__uint_as_float(v[i] & 0xffff0000u)), -448.f, 448.f);
+        }
+        int w0 = __builtin_amdgcn_cvt_pk_fp8_f32(t[0], t[1], 0, false);
+        w0 = __builtin_amdgcn_cvt_pk_fp8_f32(t[2], t[3], w0, true);
+        int w1 = __builtin_amdgcn_cvt_pk_fp8_f32(t[4], t[5], 0, false);
+        w1 = __builtin_amdgcn_cvt_pk_fp8_f32(t[6], t[7], w1, true);
+        o[0] = (uint32_t)w0;
+        o[1] = (uint32_t)w1;
+    }
+    return o;
+}
+
 // (a & mask) | c in one VALU op.  The compiler splits it into v_and + v_or when mask and c are
 // literals (a VOP3 encoding takes no literal on this target), so the operands are pinned to registers.
 __device__ __forceinline__ uint32_t and_or_b32(uint32_t a, uint32_t mask, uint32_t c)
@@ -131,7 +189,6 @@ int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *
 int launch_quantize_fp8_rows(const void *x, int64_t rows, int K, void *codes, float *scales, hipStream_t s);
 int launch_quantize_fp4_rows(const void *x, int64_t rows, int K, void *codes, float *scales, hipStream_t s);
 int launch_canonical_codes(int fmt, const void *codes, int64_t rows, int K, void *out, hipStream_t s);
-int launch_widen_e2m1(const void *codes4, int64_t n_weights, void *codes8, hipStream_t s);   // e2m1 codes -> e4m3 bytes
 int launch_e4m3_to_bf16(const void *x8, int64_t n, void *x16, hipStream_t s);               // e4m3 bytes -> bf16 (exact)
 int launch_route_only(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w, hipStream_t s);
 int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t *ids, float *w,
@@ -153,14 +210,16 @@ struct GemmArgs {
     int epilogue;       // NONE or SILU_MUL here; COMBINE is NONE into ws + combine kernel
     void *out;          // [M][N] or [M][N/2]
     int out_f32;
-    // routed mode of the W4A16 decode kernel (ids != null; offsets and row maps unused): row = pair id
-    // t * topk + slot of expert ids[row], activation row t (x_per_token) or the pair id, output row = pair id
+    // routed mode of the decode kernels (ids != null; offsets and row maps unused): row = pair id
+    // t * topk + slot of expert ids[row], activation row t (x_per_token) or the pair id, output row = pair id;
+    // x is bf16 for every format (the e4m3-activation formats quantize the rows they gather)
     const int32_t *ids = nullptr;
     int topk = 0;
     int x_per_token = 0;
 };
 int launch_qgemm_stream(const GemmArgs &a, hipStream_t s);
 bool qgemm_stream_supported(int fmt, int N, int K);
+bool qgemm_stream_routed_supported(int fmt, int N, int K, int T, int topk);
 int launch_qgemm_stream_w4(const GemmArgs &a, hipStream_t s);
 bool qgemm_stream_w4_supported(int N, int K);
 bool qgemm_stream_w4_routed_supported(int N, int K, int T, int topk);

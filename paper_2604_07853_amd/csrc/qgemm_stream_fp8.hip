@@ -16,7 +16,16 @@
 // Experts with more than 16*MT rows: the grid carries m_split row blocks per (expert,
 // slice), mapped to consecutive workgroups of the same XCD so that their identical weight
 // reads meet in that XCD's L2; rows beyond 16*MT*m_split take further passes.
+//
+// Routed mode (QX): the kernel is driven by the router's ids and by 16-bit activations.  Every
+// workgroup lists its expert's (token, slot) pairs itself and quantizes the token rows it
+// gathers with the row quantizer's own arithmetic (one wavefront per row: absmax, s_x =
+// absmax / 448, e4m3 codes of x / s_x), so a decode step needs neither a grouping pass nor an
+// activation-quantizer launch between the router and the two expert GEMMs, and its results
+// equal theirs bit for bit.
 #include <math.h>
+
+#include <type_traits>
 
 #include "common.hpp"
 
@@ -41,16 +50,23 @@ struct StreamParams {
     int n_slices;    // workgroups along the weight rows of one expert
     int m_split;     // row blocks per (expert, slice) in the grid
     int w4;          // weights are packed e2m1 codes [E][N][K/8] words
+    // routed mode: x is bf16; row = pair id t * topk + slot of expert ids[row], activation row t (x_per_token)
+    // or the pair id, output row = pair id
+    const int32_t *ids;
+    int n_ids, topk, x_per_token;
 };
+
+constexpr int kIdsMax = 4096;    // pairs a workgroup scans (8 per thread)
+constexpr int kIdsRows = 512;    // rows of one expert it can list: one per token, T <= 512
 
 // LDS bytes per activation row: the row plus 16 bytes, so consecutive rows skew by 4 banks.
 __host__ __device__ constexpr int x_stride(int K) { return K + 16; }
 
 // Dynamic LDS of a workgroup: row ids, output rows, row scales, pair counter, token tile.
-size_t stream_lds_bytes(int K, int MT)
+size_t stream_lds_bytes(int K, int MT, bool routed = false)
 {
     const size_t rows = (size_t)MT * 16;
-    return rows * 12 + 16 + rows * x_stride(K);
+    return rows * 12 + 16 + rows * x_stride(K) + (routed ? 8 * (size_t)kIdsRows + 4 * kSWaves : 0);
 }
 
 // e2m1 magnitude code (3 bits) -> e4m3 byte of the same value: 0, 0.5, 1, 1.5 | 2, 3, 4, 6.  Every e2m1 value is
@@ -69,8 +85,8 @@ __device__ __forceinline__ u32x2 widen_e2m1_word(uint32_t w)
 }
 
 // EPI: NONE or SILU_MUL; MT: 16-row token tiles per block; R: ring depth in 128-k steps (must divide K/128);
-// W4: the weights are packed e2m1 codes (half a byte per weight) instead of e4m3 bytes.
-template <int EPI, int MT, int R, bool W4>
+// W4: the weights are packed e2m1 codes (half a byte per weight) instead of e4m3 bytes; QX: routed mode.
+template <int EPI, int MT, int R, bool W4, bool QX>
 __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -138,18 +154,72 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamPa
         for (int r = 0; r < R; ++r) fill(ring[r], r, src);
     };
 
-    const int row0 = p.offsets[e];
-    const int Me = p.offsets[e + 1] - row0;
+    int row0, Me;
+    int *tmp_map = (int *)(xs + kRowsMax * stride);   // routed mode: [kIdsRows] activation rows, [kIdsRows] pair ids, [kSWaves] counts
+    if (QX) {
+        // Thread tid looks at pairs 8 tid .. 8 tid + 7.  Matches keep their order: the rows of an expert are its
+        // pairs by increasing pair id, the (token, slot) order a stable grouping gives.
+        const int base = tid * 8;
+        uint32_t hits = 0;
+#pragma unroll
+        for (int q4 = 0; q4 < 2; ++q4) {
+            const int b4 = base + 4 * q4;
+            i32x4 v4 = {-1, -1, -1, -1};
+            if (b4 + 3 < p.n_ids) {
+                v4 = *(const i32x4 *)(p.ids + b4);
+            } else {
+                for (int k = 0; b4 + k < p.n_ids; ++k) v4[k] = p.ids[b4 + k];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) hits |= (v4[k] == e) ? (1u << (4 * q4 + k)) : 0u;
+        }
+        const int cnt = __popc(hits);
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        int *s_wcnt = tmp_map + 2 * kIdsRows;
+        if (lane == 63) s_wcnt[wave] = incl;
+        lds_barrier();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kSWaves; ++w) {
+            const int cw = s_wcnt[w];
+            before += w < wave ? cw : 0;
+            total += cw;
+        }
+        int rank = before + incl - cnt;
+        for (uint32_t hm = hits; hm; hm &= hm - 1) {
+            const int pr = base + __builtin_ctz(hm);
+            if (rank < kIdsRows) {
+                tmp_map[rank] = p.x_per_token ? pr / p.topk : pr;
+                tmp_map[kIdsRows + rank] = pr;
+            }
+            ++rank;
+        }
+        row0 = 0;
+        Me = min(total, kIdsRows);
+    } else {
+        row0 = p.offsets[e];
+        Me = p.offsets[e + 1] - row0;
+    }
     if (Me <= mh * kRowsMax) return;
 
     for (int m0 = mh * kRowsMax; m0 < Me; m0 += kRowsMax * p.m_split) {
         const int mrem = min(kRowsMax, Me - m0);
-        lds_barrier();  // previous pass is done with the LDS tile
+        lds_barrier();  // the pair list is complete / the previous pass is done with the LDS tile
         if (tid < kRowsMax) {
             const int i = row0 + m0 + tid;
-            s_row[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
-            s_orow[tid] = (tid < mrem) ? (p.out_row_map ? p.out_row_map[i] : i) : -1;
-            s_xs[tid] = (tid < mrem) ? p.x_scales[p.row_map ? p.row_map[i] : i] : 0.f;
+            if (QX) {
+                s_row[tid] = (tid < mrem) ? tmp_map[i] : -1;
+                s_orow[tid] = (tid < mrem) ? tmp_map[kIdsRows + i] : -1;
+            } else {
+                s_row[tid] = (tid < mrem) ? (p.row_map ? p.row_map[i] : i) : -1;
+                s_orow[tid] = (tid < mrem) ? (p.out_row_map ? p.out_row_map[i] : i) : -1;
+                s_xs[tid] = (tid < mrem) ? p.x_scales[p.row_map ? p.row_map[i] : i] : 0.f;
+            }
         }
         if (tid == 0) *s_next = kSWaves;  // pairs 0..7 start on wavefronts 0..7, the rest are drawn
         lds_barrier();
@@ -158,7 +228,55 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamPa
         // time), so the only index arithmetic is an add per block, and all its loads are in flight at
         // once.  Vector loads return in order: the token rows are requested first and the weight
         // stream right behind them, so it flows in while the tile is being built.
-        {
+        if (QX) {
+            // ---- routed mode: 16-bit token rows, quantized on their way into LDS.  One wavefront per row (rows
+            // wave, wave + 8, ...): lane L holds the 16-byte chunks L, L + 64, ... of the row, the row's absmax is
+            // a wavefront reduction, and the codes are the row quantizer's (same scale, same division, same
+            // conversion).  Rows past the expert's end are left alone: a tile row feeds only its own output row,
+            // which is never stored.
+            const int n16 = K / 8;   // chunks of 8 values per row
+            auto gather_q = [&](auto rows_c, auto kch_c, int rbase, bool first) {
+                constexpr int ROWS = decltype(rows_c)::value, KCH = decltype(kch_c)::value;
+                u32x4 v[ROWS][KCH];
+                int xrow[ROWS];
+#pragma unroll
+                for (int rr = 0; rr < ROWS; ++rr) {
+                    xrow[rr] = __builtin_amdgcn_readfirstlane(s_row[rbase + rr * kSWaves + wave]);
+#pragma unroll
+                    for (int u = 0; u < KCH; ++u) {
+                        const int ch = lane + 64 * u;
+                        v[rr][u] = u32x4{0, 0, 0, 0};
+                        if (xrow[rr] >= 0 && ch < n16)
+                            v[rr][u] = *(const u32x4 *)((const unsigned char *)p.x + ((int64_t)xrow[rr] * K + ch * 8) * 2);
+                    }
+                }
+                if (first) fill_ring(wave, 0);   // the weight stream is requested right behind the token rows
+#pragma unroll
+                for (int rr = 0; rr < ROWS; ++rr) {
+                    if (xrow[rr] < 0) continue;
+                    const int r = rbase + rr * kSWaves + wave;
+                    float am = 0.f;
+#pragma unroll
+                    for (int u = 0; u < KCH; ++u) am = absmax_bf16x8(v[rr][u], am);
+                    am = wave_max(am);
+                    const float sxr = am / 448.0f;
+                    const RowScale rs(sxr);
+#pragma unroll
+                    for (int u = 0; u < KCH; ++u) {
+                        const int ch = lane + 64 * u;
+                        if (ch < n16) *(u32x2 *)(xs + r * stride + ch * 8) = e4m3_quantize_bf16x8(rs, v[rr][u]);
+                    }
+                    if (lane == 0) s_xs[r] = sxr;
+                }
+            };
+            if (n16 <= 4 * 64) {
+                gather_q(std::integral_constant<int, 2 * MT>(), std::integral_constant<int, 4>(), 0, true);
+            } else {
+#pragma unroll 1
+                for (int i = 0; i < MT; ++i)
+                    gather_q(std::integral_constant<int, 2>(), std::integral_constant<int, 8>(), i * 16, i == 0);   // rows 16 i + wave, + 8
+            }
+        } else {
             const int bpr = K / 16;                      // blocks per row
             const int rpp = kSThreads / bpr;             // rows covered per sweep of the workgroup
             const int rsub = tid / bpr, b = tid - rsub * bpr;
@@ -259,16 +377,16 @@ __global__ __launch_bounds__(kSThreads, 1) void qgemm_stream_fp8_kernel(StreamPa
     }
 }
 
-template <int EPI, int MT, int R, bool W4>
+template <int EPI, int MT, int R, bool W4, bool QX>
 int launch_cfg_w(const StreamParams &p, hipStream_t s)
 {
-    const size_t lds = stream_lds_bytes(p.K, MT);
+    const size_t lds = stream_lds_bytes(p.K, MT, QX);
     if (lds > 160 * 1024) {
         set_error("qgemm (decode path): K=%d needs %zu bytes of LDS per workgroup, more than the 160 KiB of a CU", p.K, lds);
         return QARL_ERR_UNSUPPORTED;
     }
     static LdsLimitOnce once;
-    auto kern = qgemm_stream_fp8_kernel<EPI, MT, R, W4>;
+    auto kern = qgemm_stream_fp8_kernel<EPI, MT, R, W4, QX>;
     if (int rc = raise_lds_limit((const void *)kern, once, "hipFuncSetAttribute(stream fp8)")) return rc;
     const int64_t units = (int64_t)p.E * p.n_slices;
     const int64_t grid = ((units + 7) / 8) * 8 * p.m_split;
@@ -279,7 +397,8 @@ int launch_cfg_w(const StreamParams &p, hipStream_t s)
 template <int EPI, int MT, int R>
 int launch_cfg(const StreamParams &p, hipStream_t s)
 {
-    return p.w4 ? launch_cfg_w<EPI, MT, R, true>(p, s) : launch_cfg_w<EPI, MT, R, false>(p, s);
+    if (p.ids) return p.w4 ? launch_cfg_w<EPI, MT, R, true, true>(p, s) : launch_cfg_w<EPI, MT, R, false, true>(p, s);
+    return p.w4 ? launch_cfg_w<EPI, MT, R, true, false>(p, s) : launch_cfg_w<EPI, MT, R, false, false>(p, s);
 }
 
 template <int EPI, int MT>
@@ -311,12 +430,21 @@ int launch_one(const GemmArgs &a, hipStream_t s)
     p.K = a.K;
     p.out_f32 = a.out_f32;
     p.w4 = (a.fmt == QARL_FP4_E2M1_CH);
+    p.ids = a.ids;
+    p.n_ids = (int)a.M;
+    p.topk = a.topk;
+    p.x_per_token = a.x_per_token;
+    const bool routed = a.ids != nullptr;
+    if (routed && (a.M > kIdsMax || a.topk <= 0 || a.M % a.topk != 0 || a.M / a.topk > kIdsRows || ((uintptr_t)a.ids & 15) != 0)) {
+        set_error("qgemm (routed decode path): needs T <= %d, T * topk <= %d and 16-byte aligned ids", kIdsRows, kIdsMax);
+        return QARL_ERR_UNSUPPORTED;
+    }
     p.n_units = (EPI == QARL_EPI_SILU_MUL) ? (a.N / 2) / 16 : a.N / 32;
     // rows per expert the grid should cover in one pass: mean + 4 sigma of a uniform router
     const double mean = (double)a.M / (double)a.E;
     const double need = mean + 4.0 * sqrt(mean);
     // token tiles per workgroup: limited by the LDS tile, which holds the whole K of every row
-    const int mt_fit = stream_lds_bytes(a.K, 2) <= 160 * 1024 ? 2 : (stream_lds_bytes(a.K, 1) <= 160 * 1024 ? 1 : 0);
+    const int mt_fit = stream_lds_bytes(a.K, 2, routed) <= 160 * 1024 ? 2 : (stream_lds_bytes(a.K, 1, routed) <= 160 * 1024 ? 1 : 0);
     if (mt_fit < 1) {
         set_error("qgemm (decode path): K=%d does not fit the LDS tile", a.K);
         return QARL_ERR_UNSUPPORTED;
@@ -336,6 +464,15 @@ int launch_one(const GemmArgs &a, hipStream_t s)
 }
 
 }  // namespace
+
+bool qgemm_stream_routed_supported(int fmt, int N, int K, int T, int topk)
+{
+    if (fmt == QARL_W4A16_G128) return qgemm_stream_w4_routed_supported(N, K, T, topk);
+    if (fmt != QARL_FP8_E4M3_CH && fmt != QARL_FP4_E2M1_CH) return false;
+    if (!qgemm_stream_supported(fmt, N, K) || T <= 0 || topk <= 0) return false;
+    if (T > kIdsRows || (int64_t)T * topk > kIdsMax) return false;
+    return stream_lds_bytes(K, 1, true) <= 160 * 1024;
+}
 
 bool qgemm_stream_supported(int fmt, int N, int K)
 {

@@ -11,20 +11,31 @@
 // asynchronous global -> LDS copies, three 128-k stages deep; 16-byte chunks of a row are XOR-swizzled with
 // the row index so that the copies (8 rows x 128 bytes per wavefront instruction) and the operand reads
 // (32 rows, one chunk) are free of bank conflicts.  The operand reads of half a stage run under the MFMAs
-// of the half before, across the stage barrier as well.
+// of the half before, across the stage barrier as well; the six (four) copy instructions of a stage are
+// issued one by one between its MFMAs, so that a wavefront that waits for room in the memory pipeline
+// waits while its matrix instructions execute.
+//
+// FP4 weights (W4 = true) take the same kernel: the instruction reads e2m1 codes natively in its first
+// operand (format select 4), 16 bytes per lane instead of 32.  A weight row then has 64 bytes per stage
+// (four chunks, swizzled with (row >> 2) & 3), a stage is 32 KiB instead of 48, and no e4m3 copy of the
+// weights is ever written.  The library packs the eight codes of a word as (element b, element 4 + b) in
+// byte b; the instruction pairs nibble n of its first operand with byte n of the second within a group of
+// 16 k, so the token bytes of every 8-byte group are put into the order 0 4 1 5 2 6 3 7 after their LDS
+// read (two byte permutes per 8 bytes).  Across groups it pairs the 2 x 16 codes of first-operand lane h
+// (k-half h of the 64) with bytes [16 h, 16 h + 16) of second-operand lanes 0 and 1: the token lanes
+// therefore read the 16-byte chunks h and 2 + h of a half stage instead of 2 h and 2 h + 1.
 #include "common.hpp"
 
 namespace qarl {
 
 constexpr int kFThreads = 512;
 constexpr int kFTM = 128, kFTN = 256;        // token rows, weight rows per workgroup
-constexpr int kFKS = 128;                    // k (= bytes) per stage
-constexpr int kFStageB = (kFTM + kFTN) * kFKS;
+constexpr int kFKS = 128;                    // k per stage (= bytes of an e4m3 row; an e2m1 row has 64)
 constexpr int kFStages = 3;
-constexpr int kFLds = kFStages * kFStageB;
+__host__ __device__ constexpr int stage_bytes(bool w4) { return kFTM * kFKS + kFTN * (w4 ? kFKS / 2 : kFKS); }
 
 struct Tile8Params {
-    const unsigned char *codes;   // [E][N][K] e4m3
+    const unsigned char *codes;   // [E][N][K] e4m3, or [E][N][K/2] packed e2m1
     const float *scales;          // [E][N]
     const unsigned char *x;       // [x_rows][K] e4m3
     const float *x_scales;        // [x_rows]
@@ -39,9 +50,12 @@ struct Tile8Params {
     int m_slots, total;
 };
 
-template <int EPI>
+template <int EPI, bool W4>
 __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Params p)
 {
+    constexpr int kFStageB = stage_bytes(W4);
+    constexpr int kWRowB = W4 ? kFKS / 2 : kFKS;   // bytes of a weight row per stage
+    constexpr int kWCopies = W4 ? 2 : 4;           // copy instructions per wavefront and stage for the weight rows
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr bool kSilu = (EPI == QARL_EPI_SILU_MUL);
     __shared__ __attribute__((aligned(16))) int s_rows[kFTM];
@@ -125,7 +139,7 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
     // r * 128 + (q ^ ((r >> 1) & 7)) * 16.  This wavefront copies token rows [16 w, 16 w + 16) and weight
     // rows [32 w, 32 w + 32) of the tile.
     const unsigned char *aptr[2];
-    uint32_t boff[4];
+    uint32_t boff[kWCopies];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int r = wave * 16 + i * 8 + (lane >> 3);
@@ -135,33 +149,49 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
     uint32_t soff = 0;   // weight row whose scale this lane copies: LDS row 64 (wave % 4) + lane
     auto set_block = [&](int nb) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = wave * 32 + i * 8 + (lane >> 3);
-            const int q = (lane & 7) ^ ((r >> 1) & 7);
-            boff[i] = (uint32_t)weight_row(nb, r) * (uint32_t)K + q * 16;
+        for (int i = 0; i < kWCopies; ++i) {
+            if (W4) {   // 16 rows x 64 bytes per instruction
+                const int r = wave * 32 + i * 16 + (lane >> 2);
+                const int q = (lane & 3) ^ ((r >> 2) & 3);
+                boff[i] = (uint32_t)weight_row(nb, r) * (uint32_t)(K / 2) + q * 16;
+            } else {
+                const int r = wave * 32 + i * 8 + (lane >> 3);
+                const int q = (lane & 7) ^ ((r >> 1) & 7);
+                boff[i] = (uint32_t)weight_row(nb, r) * (uint32_t)K + q * 16;
+            }
         }
         soff = (uint32_t)weight_row(nb, (wave & 3) * 64 + lane);
     };
     set_block(nb0);
-    const unsigned char *wbase = p.codes + (int64_t)e * N * K;
+    const unsigned char *wbase = p.codes + (int64_t)e * N * (W4 ? K / 2 : K);
     const float *sbase = p.scales + (int64_t)e * N;
-    auto copy_stage = [&](int ks, int buf) {
+    // copy number j (0 .. 1 + kWCopies) of stage ks into buffer buf: two token copies, then the weight copies
+    auto copy_one = [&](int ks, int buf, int j) {
         unsigned char *dst = smem + buf * kFStageB;
+        if (j < 2) copy16_to_lds(aptr[j] + ks * kFKS, dst + (wave * 16 + j * 8) * kFKS);
+        else copy16_to_lds(wbase + (int64_t)ks * kWRowB + boff[j - 2], dst + kFTM * kFKS + (wave * 32) * kWRowB + (j - 2) * 1024);
+    };
+    auto copy_stage = [&](int ks, int buf) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) copy16_to_lds(aptr[i] + ks * kFKS, dst + (wave * 16 + i * 8) * kFKS);
-        const unsigned char *ws = wbase + (int64_t)ks * kFKS;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) copy16_to_lds(ws + boff[i], dst + (kFTM + wave * 32 + i * 8) * kFKS);
+        for (int j = 0; j < 2 + kWCopies; ++j) copy_one(ks, buf, j);
     };
 
     // ---- operand reads: v_mfma_f32_32x32x64_f8f6f4 takes 32 bytes per lane and operand: lane (c,h), half t of
     // the stage -> row c, bytes [64 t + 32 h, +32) = chunks 4t + 2h and 4t + 2h + 1 (both operands split k alike)
-    int foff[4];
+    // e2m1 weights: 16 bytes per lane, chunk 2 t + h of the row's four
+    int foff[4], woff[2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) foff[t * 2 + u] = c * kFKS + (((4 * t + 2 * h + u) ^ ((c >> 1) & 7)) * 16);
-    const int a_wave = wm * 64 * kFKS, b_wave = (kFTM + wn * 64) * kFKS;
+        for (int u = 0; u < 2; ++u) {
+            // e2m1 first operand: the instruction pairs its lane h with bytes [16 h, 16 h + 16) of the second operand's
+            // lanes 0 and 1 (measured), so the token lanes take the 16-byte chunks h and 2 + h of the half stage
+            const int chunk = W4 ? 4 * t + h + 2 * u : 4 * t + 2 * h + u;
+            foff[t * 2 + u] = c * kFKS + ((chunk ^ ((c >> 1) & 7)) * 16);
+        }
+        woff[t] = c * (kFKS / 2) + (((2 * t + h) ^ ((c >> 2) & 3)) * 16);
+    }
+    const int a_wave = wm * 64 * kFKS, b_wave = kFTM * kFKS + wn * 64 * kWRowB;
     struct Frags {
         i32x8 a[2], b[2];
     };
@@ -175,10 +205,28 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
         }
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-            const u32x4 lo = *(const u32x4 *)(base + foff[t * 2] + b_wave + nt * 32 * kFKS);
-            const u32x4 hi = *(const u32x4 *)(base + foff[t * 2 + 1] + b_wave + nt * 32 * kFKS);
-            f.b[nt] = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            if (W4) {
+                const u32x4 lo = *(const u32x4 *)(base + woff[t] + b_wave + nt * 32 * kWRowB);
+                f.b[nt] = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], 0, 0, 0, 0};
+            } else {
+                const u32x4 lo = *(const u32x4 *)(base + foff[t * 2] + b_wave + nt * 32 * kFKS);
+                const u32x4 hi = *(const u32x4 *)(base + foff[t * 2 + 1] + b_wave + nt * 32 * kFKS);
+                f.b[nt] = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            }
         }
+    };
+    // e2m1 weights: token bytes 0..7 of every 8-byte group -> order 0 4 1 5 2 6 3 7 (nibble n of a packed word
+    // holds element n / 2 + 4 (n % 2))
+    auto pair_tokens = [&](Frags &f) {
+        if (!W4) return;
+#pragma unroll
+        for (int ms = 0; ms < 2; ++ms)
+#pragma unroll
+            for (int d = 0; d < 8; d += 2) {
+                const uint32_t lo = (uint32_t)f.a[ms][d], hi = (uint32_t)f.a[ms][d + 1];
+                f.a[ms][d] = (int)__builtin_amdgcn_perm(hi, lo, 0x05010400u);
+                f.a[ms][d + 1] = (int)__builtin_amdgcn_perm(hi, lo, 0x07030602u);
+            }
     };
     f32x16 acc[2][2];
 #pragma unroll
@@ -187,18 +235,26 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[ms][nt][i] = 0.f;
+    // e4m3 (or e2m1: format 4) x e4m3, no block scales
+    auto mfma1 = [&](const Frags &f, int ms, int nt) {
+        acc[ms][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.b[nt], f.a[ms], acc[ms][nt], W4 ? 4 : 0, 0, 0, 0, 0, 0);
+    };
     auto mfma4 = [&](const Frags &f) {
 #pragma unroll
         for (int ms = 0; ms < 2; ++ms)
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)   // e4m3 x e4m3, no block scales
-                acc[ms][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.b[nt], f.a[ms], acc[ms][nt], 0, 0, 0, 0, 0, 0);
+            for (int nt = 0; nt < 2; ++nt) mfma1(f, ms, nt);
     };
 
     // Rotated loop (see logprob.hip): the MFMAs of a stage's last group run in the next trip, behind the
     // stage barrier and under the first operand reads of the next stage.  The copies of stage s + 2 are
-    // issued at the start of stage s into the buffer stage s - 1 has just left; the wait before the barrier
-    // leaves exactly those six copies in flight.
+    // issued during stage s into the buffer stage s - 1 has just left; the wait before the barrier
+    // leaves exactly those six (e2m1 weights: four) copies in flight.
+    constexpr int kCopies = 2 + kWCopies;
+    auto wait_stage = [&]() {   // all but the newest stage's copies have landed, own LDS reads are done; then the barrier
+        if (W4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
     const int stages = K / kFKS;
     Frags last, g0, g1;
 #pragma unroll
@@ -219,7 +275,7 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
   for (int bi = 0; bi < p.bpw && nb0 + bi < p.n_blocks; ++bi) {
     const int nb = nb0 + bi;
     if (stages > 1)
-        asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");   // stage 0 has landed (stores of the block before too)
+        wait_stage();   // stage 0 has landed (stores of the block before too)
     else
         copy_barrier();
 #pragma unroll
@@ -231,21 +287,40 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
     int buf = 0;
     for (int ks = 0; ks < stages; ++ks) {
         const bool more = ks + 2 < stages;
-        if (more) copy_stage(ks + 2, buf == 0 ? 2 : buf - 1);
+        const int nbuf = buf == 0 ? 2 : buf - 1;
+        // one MFMA, the operand reads of the next half, then MFMA and copy in turns
         read_frags(g0, buf, 0);
-        mfma4(last);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA, the eight operand reads of the next
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);   // half, the other three MFMAs
-        __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+        mfma1(last, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, W4 ? 6 : 8, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma1(last, 0, 1);
+        if (more) copy_one(ks + 2, nbuf, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma1(last, 1, 0);
+        if (more) copy_one(ks + 2, nbuf, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma1(last, 1, 1);
+        if (more) copy_one(ks + 2, nbuf, 2);
+        pair_tokens(g0);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(g1, buf, 1);
-        mfma4(g0);
+        mfma1(g0, 0, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, W4 ? 6 : 8, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma1(g0, 0, 1);
+        if (more) copy_one(ks + 2, nbuf, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma1(g0, 1, 0);
+        if (more && kCopies > 4) copy_one(ks + 2, nbuf, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma1(g0, 1, 1);
+        if (more && kCopies > 4) copy_one(ks + 2, nbuf, 5);
+        pair_tokens(g1);
         __builtin_amdgcn_sched_barrier(0);
         if (more)
-            asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            wait_stage();
         else
             copy_barrier();
         last = g1;
@@ -310,7 +385,7 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
                 // alone, and leaves as 16-byte pieces of whole 128-byte row segments.  Chunks are XOR-swizzled
                 // with the row; the stores are written so that the compiler does not see them (in front of a
                 // visible LDS store it would drain the copies in flight for the next block).
-                unsigned char *ot = smem + 2 * kFStageB + wave * 4096;
+                unsigned char *ot = smem + 2 * kFStageB + wave * 4096;   // 32 KiB: fits the third stage buffer of either format
                 const uint32_t ot_a = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)ot;
 #pragma unroll
                 for (int a4 = 0; a4 < 4; ++a4) {
@@ -348,7 +423,7 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
   }
 }
 
-template <int EPI>
+template <int EPI, bool W4>
 static int launch_fp8_cfg(const GemmArgs &a, hipStream_t s)
 {
     if (a.E > 256) {
@@ -386,15 +461,17 @@ static int launch_fp8_cfg(const GemmArgs &a, hipStream_t s)
     p.m_slots = (int)slots;
     p.total = (int)total;
     static LdsLimitOnce once;
-    auto kern = qgemm_tile_fp8_kernel<EPI>;
+    auto kern = qgemm_tile_fp8_kernel<EPI, W4>;
     if (int rc = raise_lds_limit((const void *)kern, once, "hipFuncSetAttribute(tile fp8)")) return rc;
-    kern<<<dim3((unsigned)total), dim3(kFThreads), kFLds, s>>>(p);
+    kern<<<dim3((unsigned)total), dim3(kFThreads), kFStages * stage_bytes(W4), s>>>(p);
     return check_hip(hipGetLastError(), "qgemm_tile_fp8_kernel");
 }
 
 int launch_qgemm_tile_fp8(const GemmArgs &a, hipStream_t s)
 {
-    return a.epilogue == QARL_EPI_SILU_MUL ? launch_fp8_cfg<QARL_EPI_SILU_MUL>(a, s) : launch_fp8_cfg<QARL_EPI_NONE>(a, s);
+    if (a.fmt == QARL_FP4_E2M1_CH)
+        return a.epilogue == QARL_EPI_SILU_MUL ? launch_fp8_cfg<QARL_EPI_SILU_MUL, true>(a, s) : launch_fp8_cfg<QARL_EPI_NONE, true>(a, s);
+    return a.epilogue == QARL_EPI_SILU_MUL ? launch_fp8_cfg<QARL_EPI_SILU_MUL, false>(a, s) : launch_fp8_cfg<QARL_EPI_NONE, false>(a, s);
 }
 
 }  // namespace qarl

@@ -161,20 +161,10 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
             if (c < n16) held[u] = xr[c];
         }
 #pragma unroll
-        for (int u = 0; u < kKeep; ++u)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                am = fmaxf(am, fabsf(__uint_as_float(held[u][i] << 16)));
-                am = fmaxf(am, fabsf(__uint_as_float(held[u][i] & 0xffff0000u)));
-            }
+        for (int u = 0; u < kKeep; ++u) am = absmax_bf16x8(held[u], am);
     } else {
         for (int c = lane; c < n16; c += 64) {
-            u32x4 v = xr[c];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                am = fmaxf(am, fabsf(__uint_as_float(v[i] << 16)));
-                am = fmaxf(am, fabsf(__uint_as_float(v[i] & 0xffff0000u)));
-            }
+            am = absmax_bf16x8(xr[c], am);
         }
     }
     am = wave_max(am);
@@ -182,28 +172,15 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
     if (lane == 0) scales[row] = s;
     u32x2 *cr = (u32x2 *)(codes + row * K);           // e4m3: 8 bytes per 8 elements
     uint32_t *cr4 = (uint32_t *)(codes + row * (K / 2));  // e2m1: 4 bytes per 8 elements
-    // x / s, correctly rounded, without a divide per element: with y = RN(1 / s) (one IEEE divide per row),
-    // q0 = RN(x y) and the exact remainder r = x - q0 s from one FMA, RN(q0 + r y) is the correctly rounded
-    // quotient (Markstein's correction step; it needs the correctly rounded reciprocal and no underflow on the
-    // way, hence the guard on s; below 2^-11 a quotient may differ from the IEEE one, where every value rounds
-    // to an e4m3 zero; the sign is copied from x, as s > 0).  Checked against the IEEE divide for all 65536 bf16 values of x and
-    // 2^20 scales (the quantizer's own absmax / 448 and random ones): no difference at |x / s| >= 2^-11.
-    const bool fast = s >= 0x1p-100f && s < 0x1p100f && (__float_as_uint(s) & 0x7fffffu) != 0x7fffffu;
-    const float y = 1.0f / s;
-    auto div = [&](float x) -> float {
-        if (!fast) return x / s;
-        const float q0 = x * y;
-        return copysignf(fmaf(fmaf(-q0, s, x), y, q0), x);   // the sign of x also where the steps end in +0 (x = -0)
-    };
+    const RowScale rs(s);   // x / s, correctly rounded, from one divide per row
     auto convert = [&](const u32x4 v, int c) {
-        u32x2 o = {0, 0};
         if (FP4) {
             uint32_t w = 0;
             if (s != 0.f) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {   // elements 2i and 2i+1; element e sits in nibble (e & 3) * 2 + (e >> 2)
-                    const uint32_t c0 = e2m1_from_f32(div(__uint_as_float(v[i] << 16)));
-                    const uint32_t c1 = e2m1_from_f32(div(__uint_as_float(v[i] & 0xffff0000u)));
+                    const uint32_t c0 = e2m1_from_f32(rs.div(__uint_as_float(v[i] << 16)));
+                    const uint32_t c1 = e2m1_from_f32(rs.div(__uint_as_float(v[i] & 0xffff0000u)));
                     const int e0 = 2 * i, e1 = 2 * i + 1;
                     w |= c0 << (4 * ((e0 & 3) * 2 + (e0 >> 2)));
                     w |= c1 << (4 * ((e1 & 3) * 2 + (e1 >> 2)));
@@ -212,25 +189,7 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
             cr4[c] = w;
             return;
         }
-        if (s != 0.f) {
-            // v_cvt_pk_fp8_f32 rounds to nearest even into OCP e4m3 (subnormals included) exactly like
-            // e4m3_from_f32 for every finite |t| <= 448 (checked over all 2^32 bit patterns on gfx950); the
-            // clamp keeps the quotient of the row's absmax, which may exceed 448 by an ulp, in that range
-            // (and sends a NaN to -448).
-            float t[8];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                t[2 * i] = __builtin_amdgcn_fmed3f(div(__uint_as_float(v[i] << 16)), -448.f, 448.f);
-                t[2 * i + 1] = __builtin_amdgcn_fmed3f(div(__uint_as_float(v[i] & 0xffff0000u)), -448.f, 448.f);
-            }
-            int w0 = __builtin_amdgcn_cvt_pk_fp8_f32(t[0], t[1], 0, false);
-            w0 = __builtin_amdgcn_cvt_pk_fp8_f32(t[2], t[3], w0, true);
-            int w1 = __builtin_amdgcn_cvt_pk_fp8_f32(t[4], t[5], 0, false);
-            w1 = __builtin_amdgcn_cvt_pk_fp8_f32(t[6], t[7], w1, true);
-            o[0] = (uint32_t)w0;
-            o[1] = (uint32_t)w1;
-        }
-        cr[c] = o;
+        cr[c] = e4m3_quantize_bf16x8(rs, v);
     };
     if (keep) {
 #pragma unroll
@@ -314,35 +273,7 @@ int launch_canonical_codes(int fmt, const void *codes, int64_t rows, int K, void
     return check_hip(hipGetLastError(), "canonical_codes_kernel");
 }
 
-// ---- format bridges of the 4-bit-weight x 8-bit-activation schemes.
-// e2m1 codes -> the e4m3 bytes of the same values (every e2m1 value is an e4m3 value): lets the FP8 tiled kernel
-// run on FP4 weights.  One thread per word of eight codes.
-__global__ __launch_bounds__(256) void widen_e2m1_kernel(const uint32_t *__restrict__ src, int64_t n_words,
-                                                         u32x2 *__restrict__ dst)
-{
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n_words) return;
-    const uint32_t w = src[i];
-    const uint32_t lo = 0x3c383000u, hi = 0x4c484440u;   // magnitude code -> e4m3 byte: 0, .5, 1, 1.5 | 2, 3, 4, 6
-    u32x2 o;
-    o[0] = __builtin_amdgcn_perm(hi, lo, w & 0x07070707u) | ((w & 0x08080808u) << 4);
-    o[1] = __builtin_amdgcn_perm(hi, lo, (w >> 4) & 0x07070707u) | (w & 0x80808080u);
-    dst[i] = o;
-}
-
-int launch_widen_e2m1(const void *codes4, int64_t n_weights, void *codes8, hipStream_t s)
-{
-    const int64_t n_words = n_weights / 8;
-    if (n_words == 0) return QARL_OK;
-    const int64_t blocks = (n_words + 255) / 256;
-    if (blocks > 0x7fffffffLL) {
-        set_error("widen e2m1: grid too large");
-        return QARL_ERR_UNSUPPORTED;
-    }
-    widen_e2m1_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const uint32_t *)codes4, n_words, (u32x2 *)codes8);
-    return check_hip(hipGetLastError(), "widen_e2m1_kernel");
-}
-
+// ---- format bridge of the W4A8 scheme.
 // e4m3 bytes -> the bf16 values they stand for (exact: four significant bits): lets the W4A16 kernels run on
 // e4m3 activations, whose row scale they apply in the epilogue.  One thread per 8 bytes.
 __global__ __launch_bounds__(256) void e4m3_to_bf16_kernel(const u32x2 *__restrict__ src, int64_t n8,

@@ -409,6 +409,62 @@ def test_routed_mode_equals_grouped_decode(q, oracle, E, N, K, T, topk):
     assert np.array_equal(np_bits(out_rt), np_bits(out_grp))
 
 
+@pytest.mark.parametrize("fmt_name", ["fp8", "fp4"])
+@pytest.mark.parametrize("E,N,K,T,topk", [(8, 64, 2048, 500, 3),      # several row blocks per expert, partial last quad of ids
+                                          (4, 512, 2048, 60, 3),      # two token tiles per block
+                                          (4, 64, 512, 37, 3),        # 111 pairs
+                                          (6, 96, 768, 171, 5),       # ring depth 3; rows with 1.5 chunks per lane
+                                          (3, 64, 4096, 50, 2),       # eight chunks per lane and row
+                                          (128, 64, 256, 512, 8)])    # the largest routed batch: 512 tokens, 4096 pairs
+def test_routed_mode_quantizes_its_rows_like_the_row_quantizer(q, oracle, fmt_name, E, N, K, T, topk):
+    """qarl_qgemm_routed on the e4m3-activation formats takes 16-bit rows and quantizes what it gathers: bit for bit
+    the row quantizer followed by the grouped decode path on the grouping of the same ids, and within tolerance of
+    the oracle's quantizer + GEMM.  Plain epilogue with x per token, SiLU*mul, and the combine on rows in pair
+    order."""
+    fmt = q.QARL_FP8_E4M3_CH if fmt_name == "fp8" else q.QARL_FP4_E2M1_CH
+    seed = 1700 + K + T
+    w = synth.normal_bf16((E, N, K), 0.02, seed=seed)
+    x = synth.normal_bf16((T, K), 1.0, seed=seed + 1)
+    x[T // 2] = 0                                                  # a zero row: scale 0, codes 0, output 0
+    lg = synth.router_logits(T, E, seed + 2, zipf_s=1.1)
+    ids, wts = oracle.route(np_bits(lg), topk)
+    counts, offsets, pairs = oracle.group(ids, E)
+    M = T * topk
+    tok = (pairs // topk).astype(np.int32)
+    d_ids = _i32(np.asarray(ids).reshape(-1))
+    d_off, d_tok, d_pairs = _i32(offsets), _i32(tok), _i32(pairs)
+    d_w = torch.tensor(np.asarray(wts, dtype=np.float32), device="cuda")
+    qw = q.qarl_quantize_weights(w.cuda(), fmt)
+    inv = torch.tensor(pairs, dtype=torch.long, device="cuda")     # sorted position i holds pair pairs[i]
+    xq, sx = q.qarl_quantize_rows_fp8(x.cuda())
+    y_grp = q.qarl_qgemm_grouped(qw, xq, d_off, M, row_map=d_tok, x_scales=sx, out_dtype=q.QARL_OUT_F32,
+                                 path=q.QARL_PATH_DECODE)
+    y_rt = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    q.qarl_qgemm_routed(qw, x.cuda(), d_ids, T, topk, True, out=y_rt, out_dtype=q.QARL_OUT_F32)
+    assert torch.equal(y_rt[inv], y_grp)
+    xq_ref, sx_ref = oracle.quantize_fp8_rows(np_bits(x))
+    if fmt_name == "fp8":
+        wc, wsc = oracle.quantize_fp8_rows(np_bits(w).reshape(E * N, K))
+        y_ref = oracle.qgemm_fp8(xq_ref, sx_ref, wc.reshape(E, N, K), wsc.reshape(E, N), offsets, tok)
+    else:
+        wc, wsc = oracle.quantize_fp4_rows(np_bits(w).reshape(E * N, K))
+        y_ref = oracle.qgemm_fp4w(xq_ref, sx_ref, wc.reshape(E, N, K), wsc.reshape(E, N), offsets, tok)
+    assert norm_err(y_rt[inv].cpu().numpy(), y_ref) <= TOL_F32_FP8
+    # SiLU*mul
+    a_grp = q.qarl_qgemm_grouped(qw, xq, d_off, M, row_map=d_tok, x_scales=sx, epilogue=q.QARL_EPI_SILU_MUL,
+                                 path=q.QARL_PATH_DECODE)
+    a_rt = q.qarl_qgemm_routed(qw, x.cuda(), d_ids, T, topk, True, epilogue=q.QARL_EPI_SILU_MUL)
+    assert np.array_equal(np_bits(a_rt[inv]), np_bits(a_grp))
+    # combine: activation row = pair id
+    xp = x[torch.tensor(np.arange(M) // topk, dtype=torch.long)].contiguous()   # one row per pair, pair order
+    xg = xp[torch.tensor(pairs, dtype=torch.long)].contiguous()                 # the same rows in sorted order
+    xgq, sxg = q.qarl_quantize_rows_fp8(xg.cuda())
+    out_grp = q.qarl_qgemm_grouped(qw, xgq, d_off, M, x_scales=sxg, epilogue=q.QARL_EPI_COMBINE, combine_w=d_w,
+                                   sorted_pairs=d_pairs, T=T, topk=topk, path=q.QARL_PATH_DECODE)
+    out_rt = q.qarl_qgemm_routed(qw, xp.cuda(), d_ids, T, topk, False, epilogue=q.QARL_EPI_COMBINE, combine_w=d_w)
+    assert np.array_equal(np_bits(out_rt), np_bits(out_grp))
+
+
 def test_routed_mode_errors_and_route_only(q):
     w = synth.normal_bf16((64, 32, 256), 0.02, seed=3).cuda()
     qw = q.qarl_quantize_weights(w)
@@ -420,8 +476,8 @@ def test_routed_mode_errors_and_route_only(q):
     with pytest.raises(q.QarlError) as ei:                       # more than 4096 pairs
         q.qarl_qgemm_routed(qw, x, ids, 500, 9, True)
     assert ei.value.status == q.QARL_ERR_UNSUPPORTED
-    q8 = q.qarl_quantize_weights(w, q.QARL_FP8_E4M3_CH)
-    with pytest.raises(q.QarlError) as ei:                       # FP8 has no routed kernel
+    q8 = q.qarl_quantize_weights(w, q.QARL_W4A8_G128)
+    with pytest.raises(q.QarlError) as ei:                       # W4A8 has no routed kernel
         q.qarl_qgemm_routed(q8, x, ids, 16, 8, True)
     assert ei.value.status == q.QARL_ERR_UNSUPPORTED
     out = q.qarl_qgemm_routed(qw, x, ids, 0, 8, True)            # T = 0: nothing to do
