@@ -126,17 +126,6 @@ int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *
 // pass and the conversion pass, longer rows are read a second time (a cache hit).
 constexpr int kF8Threads = 256;
 
-// e2m1 code of a finite t, nearest value with ties to the even code, saturating at 6: the magnitude code is the
-// number of rounding boundaries at or below |t| (midpoints 0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5; a tie belongs to
-// the upper value exactly where that one has the even code).
-__device__ __forceinline__ uint32_t e2m1_from_f32(float t)
-{
-    const float a = fabsf(t);
-    const uint32_t m = (uint32_t)(a > 0.25f) + (uint32_t)(a >= 0.75f) + (uint32_t)(a > 1.25f) + (uint32_t)(a >= 1.75f) +
-                       (uint32_t)(a > 2.5f) + (uint32_t)(a >= 3.5f) + (uint32_t)(a > 5.0f);
-    return m | ((__float_as_uint(t) >> 28) & 8u);
-}
-
 template <bool FP4>
 __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uint16_t *__restrict__ x,
                                                                        int64_t rows, int K,
@@ -177,14 +166,20 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
         if (FP4) {
             uint32_t w = 0;
             if (s != 0.f) {
+                // v_cvt_scalef32_pk_fp4_f32 with scale 1 rounds to the nearest e2m1 value, ties to the even code,
+                // saturating at 6, and puts its two results into one byte (first source in the low nibble): byte b
+                // takes elements b and 4 + b.  Checked against a software encoder (comparisons with the seven rounding boundaries) on every boundary, its two
+                // neighbours, zeros of both signs, tiny and huge values and 2^16 random ones on gfx950: identical.
+                float t[8];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {   // elements 2i and 2i+1; element e sits in nibble (e & 3) * 2 + (e >> 2)
-                    const uint32_t c0 = e2m1_from_f32(rs.div(__uint_as_float(v[i] << 16)));
-                    const uint32_t c1 = e2m1_from_f32(rs.div(__uint_as_float(v[i] & 0xffff0000u)));
-                    const int e0 = 2 * i, e1 = 2 * i + 1;
-                    w |= c0 << (4 * ((e0 & 3) * 2 + (e0 >> 2)));
-                    w |= c1 << (4 * ((e1 & 3) * 2 + (e1 >> 2)));
+                for (int i = 0; i < 4; ++i) {
+                    t[2 * i] = rs.div(__uint_as_float(v[i] << 16));
+                    t[2 * i + 1] = rs.div(__uint_as_float(v[i] & 0xffff0000u));
                 }
+                w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[0], t[4], 1.0f, 0);
+                w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[1], t[5], 1.0f, 1);
+                w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[2], t[6], 1.0f, 2);
+                w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[3], t[7], 1.0f, 3);
             }
             cr4[c] = w;
             return;
