@@ -191,12 +191,12 @@ int qarl_grouped_dw(const void *dy_bf16, const void *x_bf16, const int32_t *row_
  *   epilogue   NONE: out [T*topk][N];  SILU_MUL: out bf16 [T*topk][N/2];
  *              COMBINE: Y staged in ws as fp32 [T*topk][N] (qarl_qgemm_workspace_bytes with M = T*topk),
  *              out [T][N] = sum over slots of combine_w[t][slot] * Y[t*topk + slot], in slot order
- * x is 16-bit for every format.  For the e4m3-activation formats FP8 and FP4 the kernel applies the activation
+ * x is 16-bit for every format.  For the e4m3-activation formats FP8, FP4 and W4A8 the kernel applies the activation
  * quantizer of eq. (2) to the rows it gathers (s_x = absmax / 448 per row, e4m3 codes of x / s_x: the arithmetic
  * of qarl_quantize_rows_fp8), so a decode step has no separate quantizer launch for x or for the intermediate.
  * Results equal those of qarl_qgemm_grouped on the DECODE path with the grouping of the same ids (after
- * qarl_quantize_rows_fp8 for FP8 / FP4), bit for bit (same kernels, same order of operations per row).
- * Supported: W4A16_G128 (N % 32 == 0, K % 256 == 0, K <= 2048), FP8_E4M3_CH and FP4_E2M1_CH (N % 32 == 0,
+ * qarl_quantize_rows_fp8 for the e4m3-activation formats), bit for bit (same kernels, same order of operations per row).
+ * Supported: W4A16_G128 and W4A8_G128 (N % 32 == 0, K % 256 == 0, K <= 2048), FP8_E4M3_CH and FP4_E2M1_CH (N % 32 == 0,
  * K % 128 == 0, K <= 4096); T <= 512, T*topk <= 4096, a token listing an expert at most once (as the router's
  * output does; rows past 512 of one expert would be dropped); ids outside [0, E) select no expert and leave their
  * output rows unwritten.  topk_ids 16-byte aligned.  Errors as for qarl_qgemm_grouped.  T == 0 is a no-op. */

@@ -17,7 +17,7 @@ QARL_OK = 0
 QARL_ERR_INVALID_ARG, QARL_ERR_UNSUPPORTED, QARL_ERR_ALIGNMENT, QARL_ERR_WORKSPACE, QARL_ERR_HIP = -1, -2, -3, -4, -5
 QARL_W4A16_G128, QARL_FP8_E4M3_CH, QARL_FP4_E2M1_CH, QARL_W4A8_G128 = 1, 2, 3, 4
 INT4_FORMATS = (QARL_W4A16_G128, QARL_W4A8_G128)          # int4 g128 codes + bf16 group scales
-ROUTED_FORMATS = (QARL_W4A16_G128, QARL_FP8_E4M3_CH, QARL_FP4_E2M1_CH)
+ROUTED_FORMATS = (QARL_W4A16_G128, QARL_FP8_E4M3_CH, QARL_FP4_E2M1_CH, QARL_W4A8_G128)
 E4M3_ACT_FORMATS = (QARL_FP8_E4M3_CH, QARL_FP4_E2M1_CH, QARL_W4A8_G128)   # e4m3 activations + row scales
 QARL_PATH_AUTO, QARL_PATH_DECODE, QARL_PATH_PREFILL = 0, 1, 2
 QARL_EPI_NONE, QARL_EPI_SILU_MUL, QARL_EPI_COMBINE = 0, 1, 2

@@ -372,7 +372,7 @@ int qarl_qgemm_routed(const qarl_qweight *W, const void *x, int x_per_token, con
     }
     if (T == 0) return QARL_OK;
     if (!qgemm_stream_routed_supported(W->fmt, W->N, W->K, T, topk)) {
-        set_error("qarl_qgemm_routed: supports W4A16 (N %% 32 == 0, K %% 256 == 0, K <= 2048), FP8 and FP4 (N %% 32 == 0, "
+        set_error("qarl_qgemm_routed: supports W4A16 and W4A8 (N %% 32 == 0, K %% 256 == 0, K <= 2048), FP8 and FP4 (N %% 32 == 0, "
                   "K %% 128 == 0, K <= 4096) with T <= 512 and T * topk <= 4096 (got fmt=%d N=%d K=%d T=%d topk=%d)",
                   W->fmt, W->N, W->K, T, topk);
         return QARL_ERR_UNSUPPORTED;

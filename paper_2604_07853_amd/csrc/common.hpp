@@ -117,13 +117,21 @@ __device__ __forceinline__ u32x2 e4m3_quantize_bf16x8(const RowScale &rs, u32x4 
     return o;
 }
 
-// (a & mask) | c in one VALU op.  The compiler splits it into v_and + v_or when mask and c are
-// literals (a VOP3 encoding takes no literal on this target), so the operands are pinned to registers.
-__device__ __forceinline__ uint32_t and_or_b32(uint32_t a, uint32_t mask, uint32_t c)
+// A constant the optimiser cannot see through, held in a scalar (vector) register.  (a & mask) | c with such operands
+// is selected as one v_and_or_b32; with literal operands the compiler emits v_and + v_or (a VOP3 encoding takes no
+// literal on this target).  The operation itself must stay an instruction the compiler knows: a matrix instruction
+// that reads a register needs wait states after the VALU instruction that wrote it, which the compiler inserts for
+// its own instructions and cannot insert for the contents of an inline asm (with v_and_or_b32 written as inline
+// asm, a matrix instruction scheduled directly behind it read the register's previous contents now and then).
+__device__ __forceinline__ uint32_t opaque_sgpr(uint32_t v)
 {
-    uint32_t d;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(c));
-    return d;
+    asm("" : "+s"(v));
+    return v;
+}
+__device__ __forceinline__ uint32_t opaque_vgpr(uint32_t v)
+{
+    asm("" : "+v"(v));
+    return v;
 }
 
 // Bit position of the low bit of element e (0..7) of a packed word of int4 codes (stored as u = q+8).
@@ -138,12 +146,12 @@ __host__ __device__ constexpr int int4_bit_pos(int e) { return e < 6 ? 3 + 4 * (
 // the first pair, a shift (or the rotation) and an and-or for each of the other three.
 __device__ __forceinline__ bf16x8 unpack_int4_word(uint32_t w)
 {
-    const uint32_t mask = 0x00780078u, one = 0x3f803f80u;
+    const uint32_t mask = opaque_sgpr(0x00780078u), one = opaque_vgpr(0x3f803f80u);
     u32x4 d;
-    d[0] = and_or_b32(w, mask, one);
-    d[1] = and_or_b32(w >> 4, mask, one);
-    d[2] = and_or_b32(w >> 8, mask, one);
-    d[3] = and_or_b32(__builtin_rotateright32(w, 12), mask, one);
+    d[0] = (w & mask) | one;
+    d[1] = ((w >> 4) & mask) | one;
+    d[2] = ((w >> 8) & mask) | one;
+    d[3] = (__builtin_rotateright32(w, 12) & mask) | one;
     return __builtin_bit_cast(bf16x8, d);
 }
 

@@ -467,7 +467,7 @@ int launch_one(const GemmArgs &a, hipStream_t s)
 
 bool qgemm_stream_routed_supported(int fmt, int N, int K, int T, int topk)
 {
-    if (fmt == QARL_W4A16_G128) return qgemm_stream_w4_routed_supported(N, K, T, topk);
+    if (fmt == QARL_W4A16_G128 || fmt == QARL_W4A8_G128) return qgemm_stream_w4_routed_supported(N, K, T, topk);
     if (fmt != QARL_FP8_E4M3_CH && fmt != QARL_FP4_E2M1_CH) return false;
     if (!qgemm_stream_supported(fmt, N, K) || T <= 0 || topk <= 0) return false;
     if (T > kIdsRows || (int64_t)T * topk > kIdsMax) return false;

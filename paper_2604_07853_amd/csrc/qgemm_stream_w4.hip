@@ -72,7 +72,12 @@ struct W4Params {
     int n_ids;         // T * topk <= kIdsMax
     int topk;
     int x_per_token;   // activation row of pair pr: pr / topk if set, else pr
+    // Routed W4A8: x holds 16-bit rows; the workgroup applies the activation quantizer of eq. (2) to the rows it
+    // gathers (the row quantizer's arithmetic), keeps the e4m3 values as exact bf16 in the LDS tile and the row
+    // scales in LDS for the epilogue.
+    int qx;
 };
+constexpr int kQxScaleBytes = 4 * 64;   // LDS for the row scales of a block (up to 64 rows), routed mode
 
 constexpr int kIdsMax = 4096;    // pairs a workgroup scans (8 per thread)
 constexpr int kIdsRows = 512;    // rows of one expert it can list: one per token, T <= 512
@@ -200,6 +205,7 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_kernel(W4Params p
     // this expert's pairs, [kIdsRows] pair ids, then the pair count of every wavefront's share of the ids
     int *tmp_map = (int *)(p.map_mode == 2 ? xs + kRows * stride : xs);
     const int m4 = routed ? kIdsRows : (p.M + 3) & ~3;
+    float *s_rsc = (float *)(xs + kRows * stride + 8 * kIdsRows + 4 * kWaves);   // [kIdx] row scales (routed W4A8)
     int row0, Me;
     if (routed) {
         // Thread tid looks at pairs 8 tid .. 8 tid + 7.  Matches keep their order: the rows of an expert are its
@@ -297,6 +303,70 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_kernel(W4Params p
         }
         if (tid == 0) *s_next = kWaves;  // pairs 0..7 start on wavefronts 0..7, the rest are drawn
         if (!use_tmp) lds_barrier();
+        if (p.qx) {
+            // ---- routed W4A8: one wavefront per row (rows wave, wave + 8, ...), four rows in flight: lane L holds
+            // the 16-byte chunks L, L + 64, ... of the row; absmax by a wavefront reduction, s_x = absmax / 448,
+            // e4m3 codes of x / s_x (the row quantizer's arithmetic), kept as the bf16 values they stand for.
+            const int n16 = K / 8;
+            bool first = true;
+#pragma unroll 1
+            for (int rb = 0; rb < kRows; rb += 4 * kWaves) {
+                u32x4 v[4][4];
+                int xrow[4];
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int r = rb + rr * kWaves + wave;
+                    xrow[rr] = r < mrem ? __builtin_amdgcn_readfirstlane(tmp_map[row0 + m0 + r]) : -1;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int ch = lane + 64 * u;
+                        v[rr][u] = u32x4{0, 0, 0, 0};
+                        if (xrow[rr] >= 0 && ch < n16)
+                            v[rr][u] = *(const u32x4 *)((const unsigned char *)p.x + ((uint32_t)xrow[rr] * (uint32_t)K + ch * 8) * 2u);
+                    }
+                }
+                if (first) {
+                    load_scales(wave);
+                    fill_ring(wave, 0);
+                    first = false;
+                }
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int r = rb + rr * kWaves + wave;
+                    if (r >= kRows) continue;
+                    if (xrow[rr] < 0) {   // past the expert's end: a row of zeros
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            if (lane + 64 * u < n16) *(u32x4 *)(xs + r * stride + (lane + 64 * u) * 16) = u32x4{0, 0, 0, 0};
+                        if (lane == 0) s_rsc[r] = 0.f;
+                        continue;
+                    }
+                    float am = 0.f;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) am = absmax_bf16x8(v[rr][u], am);
+                    am = wave_max(am);
+                    const float sxr = am / 448.0f;
+                    const RowScale rs(sxr);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int ch = lane + 64 * u;
+                        if (ch < n16) {
+                            const u32x2 q8 = e4m3_quantize_bf16x8(rs, v[rr][u]);
+                            u32x4 o;   // e4m3 -> fp32 is exact, and so is its upper half as bf16 (four significant bits)
+#pragma unroll
+                            for (int i = 0; i < 2; ++i) {
+                                const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)q8[i], false);
+                                const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)q8[i], true);
+                                o[2 * i] = (__float_as_uint(lo[0]) >> 16) | (__float_as_uint(lo[1]) & 0xffff0000u);
+                                o[2 * i + 1] = (__float_as_uint(hi[0]) >> 16) | (__float_as_uint(hi[1]) & 0xffff0000u);
+                            }
+                            *(u32x4 *)(xs + r * stride + ch * 16) = o;
+                        }
+                    }
+                    if (lane == 0) s_rsc[r] = sxr;
+                }
+            }
+        } else
         // ---- gather the token rows into LDS (whole K) in 16-byte blocks.  A thread keeps one block column and
         // walks down the rows; the row ids are read first and then every load goes out at once, so no load
         // waits for a branch on an id.  Vector loads return in order: the token rows are requested first and the
@@ -416,7 +486,11 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_kernel(W4Params p
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
                     const i32x4 orow4 = *(const i32x4 *)(s_orow + mt * 32 + 8 * i4 + 4 * h);
-                    if (p.x_scales) {   // W4A8: the row scale s_x of eq. (2), in front of SiLU
+                    if (p.qx) {   // routed W4A8: the row scales this workgroup computed
+                        const f32x4 sc4 = *(const f32x4 *)(s_rsc + mt * 32 + 8 * i4 + 4 * h);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[mt][i4 * 4 + i] *= sc4[i];
+                    } else if (p.x_scales) {   // W4A8: the row scale s_x of eq. (2), in front of SiLU
                         const i32x4 xrow4 = *(const i32x4 *)(s_row + mt * 32 + 8 * i4 + 4 * h);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) acc[mt][i4 * 4 + i] *= p.x_scales[xrow4[i]];
@@ -673,11 +747,6 @@ __global__ __launch_bounds__(kThreads, 1) void qgemm_stream_w4_wide_kernel(W4Par
                                     const bf16x8 a = *(const bf16x8 *)(xs + (mt * 32 + m32) * stride +
                                                                        (g * 128 + L * 64 + h * 32 + jj * 8) * 2);
                                     ag[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bw, ag[mt], 0, 0, 0);
-                                    // Scheduling fence.  Without it the compiler sinks the LDS reads that initialise the
-                                    // second accumulator below this instruction and lets them land in the registers that
-                                    // hold this instruction's A operand; on the device the first row tile then came out
-                                    // corrupted (any fence here, even an empty one, gives correct results; measured).
-                                    asm volatile("s_nop 0" ::: "memory");
                                 }
                             }
                         // scale of group g0 + r: bf16 number 2 (g0 / 4) + r / 2 .. of the lane's eight (g0 is 0 or 4)
@@ -763,7 +832,7 @@ template <int EPI, int MT, int R, bool NT, bool HALF = false>
 int launch_cfg_nt(const W4Params &p, hipStream_t s)
 {
     size_t lds = lds_bytes(p.K, MT, HALF);
-    if (p.ids) lds += 8 * (size_t)kIdsRows + 4 * kWaves;
+    if (p.ids) lds += 8 * (size_t)kIdsRows + 4 * kWaves + kQxScaleBytes;
     else if (p.map_mode == 2) lds += 8 * (size_t)((p.M + 3) & ~3);
     if (lds > 160 * 1024) {
         set_error("qgemm (decode path): K=%d needs %zu bytes of LDS per workgroup, more than the 160 KiB of a CU", p.K, lds);
@@ -818,6 +887,7 @@ int launch_one(const GemmArgs &a, hipStream_t s)
     p.n_ids = a.ids ? (int)a.M : 0;
     p.topk = a.topk;
     p.x_per_token = a.x_per_token;
+    p.qx = (a.ids && a.fmt == QARL_W4A8_G128) ? 1 : 0;
     p.n_units = (EPI == QARL_EPI_SILU_MUL) ? (a.N / 2) / 16 : a.N / 32;
     // rows per expert the grid should cover in one pass: mean + 4 sigma of a uniform router
     const double mean = (double)a.M / (double)a.E;
@@ -840,7 +910,7 @@ int launch_one(const GemmArgs &a, hipStream_t s)
     // 64-row blocks over a K-chunked tile: K = 2048 (two chunks of eight scale groups), more than 32 rows per expert
     // to expect, and a slice that gives every wavefront the same one to three pairs
     static_assert(kWaves * 8 == 64, "the wide kernel's gather: eight rows per wavefront");
-    if (MT == 1 && !p.half_tile && need > 32.0 && a.K == 2048) {
+    if (MT == 1 && !p.half_tile && need > 32.0 && a.K == 2048 && !p.qx) {   // (its gather is an asynchronous copy: no quantizer)
         const int ms_w = (int)ceil(need / 64.0);
         int msh_w = 0;
         while ((1 << msh_w) < ms_w && msh_w < 3) ++msh_w;
@@ -914,7 +984,7 @@ bool qgemm_stream_w4_routed_supported(int N, int K, int T, int topk)
 {
     if (!qgemm_stream_w4_supported(N, K) || K > 2048 || T <= 0 || topk <= 0) return false;
     if (T > kIdsRows || (int64_t)T * topk > kIdsMax) return false;
-    return lds_bytes(K, 1) + 8 * (size_t)kIdsRows + 4 * kWaves <= 160 * 1024;
+    return lds_bytes(K, 1) + 8 * (size_t)kIdsRows + 4 * kWaves + kQxScaleBytes <= 160 * 1024;
 }
 
 int launch_qgemm_stream_w4(const GemmArgs &a, hipStream_t s)

@@ -257,6 +257,54 @@ def test_fp8_config4(q, oracle, T, path):
     assert torch.equal(out2.view(torch.int16), out_gpu.view(torch.int16))
 
 
+@pytest.mark.parametrize("T,path", [(256, 1), (8192, 2)])
+def test_fp4_full_size(q, oracle, T, path):
+    """The FP4 (e2m1 weights, e4m3 activations) layer at the sizes the benchmark times: codes of the whole gate_up
+    tensor through the canonical export against the oracle's quantizer, then sampled rows of gate_up (SiLU*mul) and of
+    down on the GPU's own intermediate: 256 tokens on the decode path (also driven by the router's ids), 8192 tokens
+    on the tiled path, where the matrix instruction reads the e2m1 codes natively."""
+    rng = np.random.default_rng(600 + T)
+    gu, dn = synth.expert_weights(E, H, I, seed=600, device="cuda")
+    qgu = q.qarl_quantize_weights(gu, q.QARL_FP4_E2M1_CH)
+    qdn = q.qarl_quantize_weights(dn, q.QARL_FP4_E2M1_CH)
+    guq, gus = oracle.quantize_fp4_rows(np_bits(gu))      # one code per byte
+    dnq, dns = oracle.quantize_fp4_rows(np_bits(dn))
+    del gu, dn
+    for qw, c, s in ((qgu, guq, gus), (qdn, dnq, dns)):
+        canon = q.qarl_codes_to_canonical(qw).cpu().numpy().view(np.uint8).reshape(c.shape[:-1] + (c.shape[-1] // 2,))
+        assert np.array_equal(canon & 15, c[..., 0::2]) and np.array_equal(canon >> 4, c[..., 1::2])
+        assert np.array_equal(qw.scales.cpu().numpy().reshape(s.shape), s)
+        del canon
+    x = synth.normal_bf16((T, H), 1.0, seed=601 + T, device="cuda")
+    lg = synth.router_logits(T, E, seed=602 + T, device="cuda")
+    r, w, offsets, pairs = _check_route(q, oracle, lg, T)
+    M = T * TOPK
+    tok = (pairs // TOPK).astype(np.int32)
+    layer = q.MoELayer(qgu, qdn, T, TOPK, path)
+    xq, sx = q.qarl_quantize_rows_fp8(x)
+    xq_ref, sx_ref = oracle.quantize_fp8_rows(np_bits(x))
+    a_gpu = q.qarl_qgemm_grouped(qgu, xq, r.offsets, M, row_map=r.tokens, x_scales=sx,
+                                 epilogue=q.QARL_EPI_SILU_MUL, path=path, ws=layer.ws)
+    rows = _sample_rows(offsets, rng, tile=128)
+    sub = _sub_offsets(rows, offsets)
+    a_ref_bits, a_ref = oracle.silu_mul(oracle.qgemm_fp4w(xq_ref, sx_ref, guq, gus, sub, tok[rows]))
+    a_rows = a_gpu[torch.from_numpy(rows).cuda()]
+    ea = norm_err_bf16(a_rows.float().cpu().numpy(), a_ref)
+    assert ea <= TOL_BF16, ea
+    assert flip_fraction(np_bits(a_rows), a_ref_bits) <= MAX_FLIPS_FP8
+    aq, sa = q.qarl_quantize_rows_fp8(a_gpu)
+    aq_h, sa_h = aq.cpu().numpy(), sa.cpu().numpy()
+    y_gpu = q.qarl_qgemm_grouped(qdn, aq, r.offsets, M, x_scales=sa, out_dtype=q.QARL_OUT_F32, path=path, ws=layer.ws)
+    y_ref = oracle.qgemm_fp4w(aq_h[rows], sa_h[rows], dnq, dns, sub)
+    ey = norm_err(y_gpu[torch.from_numpy(rows).cuda()].cpu().numpy(), y_ref)
+    assert ey <= TOL_F32_FP8, ey
+    del y_gpu
+    out_gpu = q.qarl_qgemm_grouped(qdn, aq, r.offsets, M, x_scales=sa, epilogue=q.QARL_EPI_COMBINE,
+                                   combine_w=r.w, sorted_pairs=r.pairs, T=T, topk=TOPK, path=path, ws=layer.ws)
+    out2 = layer.forward(x, lg)            # at 256 tokens the layer runs the routed kernels on 16-bit rows
+    assert torch.equal(out2.view(torch.int16), out_gpu.view(torch.int16))
+
+
 def test_logprob_config3_and_path_mismatch(q, oracle, layer_int4):
     """Config 3's second half: the LM head [151936, 2048] over 16384 hidden states with the fused
     per-token log-prob, sampled rows against the oracle; then the comparison the method exists for:

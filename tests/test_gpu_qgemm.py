@@ -409,7 +409,7 @@ def test_routed_mode_equals_grouped_decode(q, oracle, E, N, K, T, topk):
     assert np.array_equal(np_bits(out_rt), np_bits(out_grp))
 
 
-@pytest.mark.parametrize("fmt_name", ["fp8", "fp4"])
+@pytest.mark.parametrize("fmt_name", ["fp8", "fp4", "w4a8"])
 @pytest.mark.parametrize("E,N,K,T,topk", [(8, 64, 2048, 500, 3),      # several row blocks per expert, partial last quad of ids
                                           (4, 512, 2048, 60, 3),      # two token tiles per block
                                           (4, 64, 512, 37, 3),        # 111 pairs
@@ -421,7 +421,9 @@ def test_routed_mode_quantizes_its_rows_like_the_row_quantizer(q, oracle, fmt_na
     the row quantizer followed by the grouped decode path on the grouping of the same ids, and within tolerance of
     the oracle's quantizer + GEMM.  Plain epilogue with x per token, SiLU*mul, and the combine on rows in pair
     order."""
-    fmt = q.QARL_FP8_E4M3_CH if fmt_name == "fp8" else q.QARL_FP4_E2M1_CH
+    fmt = {"fp8": q.QARL_FP8_E4M3_CH, "fp4": q.QARL_FP4_E2M1_CH, "w4a8": q.QARL_W4A8_G128}[fmt_name]
+    if fmt_name == "w4a8" and (K % 256 or K > 2048):
+        pytest.skip("the int4 decode kernel's routed mode takes K % 256 == 0 up to 2048")
     seed = 1700 + K + T
     w = synth.normal_bf16((E, N, K), 0.02, seed=seed)
     x = synth.normal_bf16((T, K), 1.0, seed=seed + 1)
@@ -446,10 +448,13 @@ def test_routed_mode_quantizes_its_rows_like_the_row_quantizer(q, oracle, fmt_na
     if fmt_name == "fp8":
         wc, wsc = oracle.quantize_fp8_rows(np_bits(w).reshape(E * N, K))
         y_ref = oracle.qgemm_fp8(xq_ref, sx_ref, wc.reshape(E, N, K), wsc.reshape(E, N), offsets, tok)
-    else:
+    elif fmt_name == "fp4":
         wc, wsc = oracle.quantize_fp4_rows(np_bits(w).reshape(E * N, K))
         y_ref = oracle.qgemm_fp4w(xq_ref, sx_ref, wc.reshape(E, N, K), wsc.reshape(E, N), offsets, tok)
-    assert norm_err(y_rt[inv].cpu().numpy(), y_ref) <= TOL_F32_FP8
+    else:
+        c4, s4 = oracle.quantize_int4(np_bits(w))
+        y_ref = oracle.qgemm_w4a8(xq_ref, sx_ref, c4, s4, offsets, tok)
+    assert norm_err(y_rt[inv].cpu().numpy(), y_ref) <= (TOL_F32 if fmt_name == "w4a8" else TOL_F32_FP8)
     # SiLU*mul
     a_grp = q.qarl_qgemm_grouped(qw, xq, d_off, M, row_map=d_tok, x_scales=sx, epilogue=q.QARL_EPI_SILU_MUL,
                                  path=q.QARL_PATH_DECODE)
@@ -476,9 +481,9 @@ def test_routed_mode_errors_and_route_only(q):
     with pytest.raises(q.QarlError) as ei:                       # more than 4096 pairs
         q.qarl_qgemm_routed(qw, x, ids, 500, 9, True)
     assert ei.value.status == q.QARL_ERR_UNSUPPORTED
-    q8 = q.qarl_quantize_weights(w, q.QARL_W4A8_G128)
-    with pytest.raises(q.QarlError) as ei:                       # W4A8 has no routed kernel
-        q.qarl_qgemm_routed(q8, x, ids, 16, 8, True)
+    q8 = q.qarl_quantize_weights(synth.normal_bf16((4, 32, 4096), 0.02, seed=5).cuda(), q.QARL_W4A8_G128)
+    with pytest.raises(q.QarlError) as ei:                       # the int4 kernels' routed mode stops at K = 2048
+        q.qarl_qgemm_routed(q8, synth.normal_bf16((16, 4096), 1.0, seed=6).cuda(), ids, 16, 8, True)
     assert ei.value.status == q.QARL_ERR_UNSUPPORTED
     out = q.qarl_qgemm_routed(qw, x, ids, 0, 8, True)            # T = 0: nothing to do
     assert out.shape[0] == 0
