@@ -405,11 +405,13 @@ template <int EPI, int MT>
 int launch_ring(const StreamParams &p, hipStream_t s)
 {
     const int G = p.K / kGroup;
-    // ring depth (steps in flight per wavefront): four 2 KiB loads per tile already saturate HBM with eight
-    // wavefronts per CU, and a deeper ring would push the gather of the token rows into spilling
-    if (G % 4 == 0) return launch_cfg<EPI, MT, 4>(p, s);
-    if (G % 3 == 0) return launch_cfg<EPI, MT, 3>(p, s);
+    // ring depth (steps in flight per wavefront): 8 KiB per wavefront, i.e. two steps of e4m3 codes (4 KiB each: two
+    // tiles, two 1 KiB loads per tile) or four steps of e2m1 codes, already saturate HBM with eight wavefronts per CU;
+    // twice that measured 4 % slower on the gate_up launch, and a deeper ring would push the gather into spilling
+    if (p.w4 && G % 4 == 0) return launch_cfg<EPI, MT, 4>(p, s);
+    if (p.w4 && G % 3 == 0) return launch_cfg<EPI, MT, 3>(p, s);
     if (G % 2 == 0) return launch_cfg<EPI, MT, 2>(p, s);
+    if (G % 3 == 0) return launch_cfg<EPI, MT, 3>(p, s);
     return launch_cfg<EPI, MT, 1>(p, s);
 }
 
