@@ -470,6 +470,39 @@ def test_routed_mode_quantizes_its_rows_like_the_row_quantizer(q, oracle, fmt_na
     assert np.array_equal(np_bits(out_rt), np_bits(out_grp))
 
 
+@pytest.mark.parametrize("fmt_name", ["fp8", "w4a8"])
+def test_routed_mode_rows_outside_the_fast_division_range(q, oracle, fmt_name):
+    """Rows whose scale leaves the range of the corrected-reciprocal division (absmax near 2^-100 and near 2^100),
+    a zero row, negative zeros and a row of one repeated value: the kernel that quantizes its own rows must fall back
+    to the IEEE division exactly where the row quantizer does, so routed and grouped results stay bit-identical, and
+    the codes the grouped path consumed are the oracle's."""
+    fmt = q.QARL_FP8_E4M3_CH if fmt_name == "fp8" else q.QARL_W4A8_G128
+    E, N, K, T, topk = 4, 64, 512, 40, 2
+    w = synth.normal_bf16((E, N, K), 0.02, seed=1901)
+    x = synth.normal_bf16((T, K), 1.0, seed=1902).float()
+    x[0] *= 2.0 ** -110
+    x[1] *= 2.0 ** 115
+    x[2] = 0
+    x[3] = 0.375
+    x[4, :9] = -0.0
+    x[5] *= 2.0 ** -126            # bf16 subnormals
+    x = x.to(torch.bfloat16)
+    lg = synth.router_logits(T, E, 1903)
+    ids, _ = oracle.route(np_bits(lg), topk)
+    counts, offsets, pairs = oracle.group(ids, E)
+    M = T * topk
+    tok = (pairs // topk).astype(np.int32)
+    qw = q.qarl_quantize_weights(w.cuda(), fmt)
+    xq, sx = q.qarl_quantize_rows_fp8(x.cuda())
+    xq_ref, sx_ref = oracle.quantize_fp8_rows(np_bits(x))
+    assert np.array_equal(xq.cpu().numpy(), xq_ref) and np.array_equal(sx.cpu().numpy(), sx_ref)
+    y_grp = q.qarl_qgemm_grouped(qw, xq, _i32(offsets), M, row_map=_i32(tok), x_scales=sx, out_dtype=q.QARL_OUT_F32,
+                                 path=q.QARL_PATH_DECODE)
+    y_rt = q.qarl_qgemm_routed(qw, x.cuda(), _i32(np.asarray(ids).reshape(-1)), T, topk, True, out_dtype=q.QARL_OUT_F32)
+    inv = torch.tensor(pairs, dtype=torch.long, device="cuda")
+    assert torch.equal(y_rt[inv].view(torch.int32), y_grp.view(torch.int32))
+
+
 def test_routed_mode_errors_and_route_only(q):
     w = synth.normal_bf16((64, 32, 256), 0.02, seed=3).cuda()
     qw = q.qarl_quantize_weights(w)
