@@ -5,14 +5,17 @@
 //     dW[e][n][k] = sum_{i in expert e} dY[i][n] * x[row(i)][k]  -> grouped_dw_kernel
 // Both are dense contractions on v_mfma_f32_32x32x16_bf16 with fp32 accumulation.  In both the contraction index
 // is the one the operands do NOT store contiguously (n for dX: the codes are packed along k; the token index for
-// dW), so operand tiles are transposed on their way into LDS.
+// dW), while the matrix instruction wants 8 consecutive contraction elements per lane.  The tiles go to LDS as
+// they are stored (rows = contraction index, 16-byte pieces) and are read with the transposing LDS read
+// ds_read_b64_tr_b16, which hands a lane four consecutive ROWS of one column: within each group of 16 lanes, lane
+// 4 a + b receives element b of the 8 bytes addressed by lanes a, a + 4, a + 8 and a + 12 of the group.
 //
 // dX.  A workgroup owns 128 rows x 128 output columns k, i.e. exactly one scale group g of every weight row, so
 // the scale s[n][g] depends on the contraction index alone and is folded into the gradient operand:
 // A'[i][n] = bf16(dY[i][n] * s[n][g]), rounded once (the 16-bit backward; a one-hot dY and the exact-integer
 // regime stay exact).  The codes go through the same exponent trick as in the forward, (q+24)/16 as an exact
-// bf16, written k-major into LDS; the offset is removed at the end with the row sums of A' (fp32, accumulated
-// while A' is staged): dX = 16 * acc - 24 * rowsum.
+// bf16, written row by row ([n][k]) into LDS; the offset is removed at the end with the row sums of A' (fp32,
+// accumulated while A' is staged): dX = 16 * acc - 24 * rowsum.
 #include "common.hpp"
 
 namespace qarl {
@@ -36,10 +39,33 @@ struct DxParams {
     int m_slots, total;
 };
 
-// 16-byte chunk swizzles.  As: rows are gradient rows, read by 32 consecutive rows at once.  Bt: rows are output
-// columns k, read by 32 consecutive k at once and written by four 32-k ranges at once.
+// 16-byte chunk swizzles of 256-byte LDS rows.  As: rows are gradient rows, read by 32 consecutive rows at once.
+// Tiles read by the transposing read: a 32-lane pass touches four consecutive rows (from a multiple of four) and 64
+// bytes of each, so the rows go to different quarters of the 256 bytes; the second term spreads the sixteen rows a
+// code block is written to.
 __device__ __forceinline__ int swz_a(int m) { return m & 15; }
-__device__ __forceinline__ int swz_b(int k) { return (k & 15) ^ (((k >> 5) & 3) << 2); }
+__device__ __forceinline__ int swz_tr(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// MFMA operand of lane `lane` (row or column l % 32, contraction elements 8 (l / 32) .. + 7) from a tile stored
+// [contraction index][128 columns] bf16 in 256-byte rows with swz_tr chunks: contraction rows kk0 .. kk0 + 15,
+// columns col0 .. col0 + 31.
+__device__ __forceinline__ bf16x8 read_operand_tr(const unsigned char *tile, int kk0, int col0, int lane)
+{
+    const int r16 = lane & 15, g = lane >> 4;
+    const int row = kk0 + 8 * (g >> 1) + (r16 >> 2);          // the row this lane ADDRESSES (second read: + 4)
+    const int colq = col0 + 16 * (g & 1) + 4 * (r16 & 3);     // first of the four columns it addresses
+    const unsigned char *a0 = tile + row * 256 + (((colq >> 3) ^ swz_tr(row)) << 4) + (colq & 4) * 2;
+    const unsigned char *a1 = tile + (row + 4) * 256 + (((colq >> 3) ^ swz_tr(row + 4)) << 4) + (colq & 4) * 2;
+    struct {
+        s16x4 lo, hi;
+    } v;
+    v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
+    v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a1);
+    return __builtin_bit_cast(bf16x8, v);
+}
 
 __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
 {
@@ -47,7 +73,7 @@ __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
     __shared__ __attribute__((aligned(16))) int s_orow[kTM];
     __shared__ __attribute__((aligned(16))) float s_rs[kTM];
     unsigned char *As = smem;                       // [kTM][kStageN] bf16, 256-byte rows
-    unsigned char *Bt = smem + kTM * kStageN * 2;   // [kTK][kStageN] bf16, 256-byte rows
+    unsigned char *Bs = smem + kTM * kStageN * 2;   // [kStageN n][kTK k] bf16 (q+24)/16, 256-byte rows
     float *sc = (float *)(smem + (kTM + kTK) * kStageN * 2);   // [N] scales of group g as fp32
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -97,6 +123,7 @@ __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
     // gradient staging: chunk id = tid + 512 u -> row id >> 4, 16-byte piece id & 15 of the stage's 128 n
     const int am = tid >> 4, acn = tid & 15;
     float rowsum[4] = {0.f, 0.f, 0.f, 0.f};
+    const bf16x2 ones2 = __builtin_bit_cast(bf16x2, 0x3f803f80u);
     // weight staging: this wavefront expands the block of rows n0 + 16 wave .. + 15; lane = (k range q, row c)
     const int bq = lane >> 4, bc = lane & 15;
     // matrix phase: wavefront (wm, wk) owns rows 32 wm .. + 31, columns 64 wk .. + 63
@@ -127,25 +154,20 @@ __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float s0 = i < 2 ? s_lo[2 * i] : s_hi[2 * i - 4], s1 = i < 2 ? s_lo[2 * i + 1] : s_hi[2 * i - 3];
-                const uint32_t b0 = f32_to_bf16_hw(__uint_as_float(gv[u][i] << 16) * s0);
-                const uint32_t b1 = f32_to_bf16_hw(__uint_as_float(gv[u][i] & 0xffff0000u) * s1);
-                rowsum[u] += bf16_bits_to_f32(b0) + bf16_bits_to_f32(b1);
-                o[i] = b0 | (b1 << 16);
+                bf16x2 pr;
+                pr[0] = (__bf16)(__uint_as_float(gv[u][i] << 16) * s0);
+                pr[1] = (__bf16)(__uint_as_float(gv[u][i] & 0xffff0000u) * s1);
+                // row sum of the ROUNDED values: both halves times 1.0, added to the running sum in one operation
+                rowsum[u] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, rowsum[u], false);
+                o[i] = __builtin_bit_cast(uint32_t, pr);
             }
             *(u32x4 *)(As + m * 256 + ((acn ^ swz_a(m)) << 4)) = o;
         }
         {
-            const int nl = wave * 16 + bc;   // row of the stage
+            const int nl = wave * 16 + bc;   // row of the stage; word j of the lane = columns 32 bq + 8 j .. + 7
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const u32x4 d = __builtin_bit_cast(u32x4, unpack_int4_word(wv[j]));
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int k = bq * 32 + j * 8 + i;
-                    const uint16_t val = (uint16_t)(d[i >> 1] >> (16 * (i & 1)));
-                    *(uint16_t *)(Bt + k * 256 + (((nl >> 3) ^ swz_b(k)) << 4) + (nl & 7) * 2) = val;
-                }
-            }
+            for (int j = 0; j < 4; ++j)
+                *(u32x4 *)(Bs + nl * 256 + (((bq * 4 + j) ^ swz_tr(nl)) << 4)) = __builtin_bit_cast(u32x4, unpack_int4_word(wv[j]));
         }
         lds_barrier();
 #pragma unroll
@@ -155,8 +177,7 @@ __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
             const bf16x8 a = *(const bf16x8 *)(As + m * 256 + ((ch ^ swz_a(m)) << 4));
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
-                const int k = wk * 64 + kt * 32 + m32;
-                const bf16x8 b = *(const bf16x8 *)(Bt + k * 256 + ((ch ^ swz_b(k)) << 4));
+                const bf16x8 b = read_operand_tr(Bs, st * 16, wk * 64 + kt * 32, lane);
                 acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[kt], 0, 0, 0);
             }
         }
@@ -200,13 +221,10 @@ struct DwParams {
     int E, N, K, out_f32;
 };
 
-// 16-byte chunk swizzle of the k-major (token-minor) tiles: rows of 128 bytes, read by 32 consecutive rows at once
-__device__ __forceinline__ int swz_t(int r) { return (r >> 1) & 7; }
-
 __global__ __launch_bounds__(kBwThreads, 4) void grouped_dw_kernel(DwParams p)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char Yt[kTM * kStageM * 2];   // [128 n][64 m] bf16
-    __shared__ __attribute__((aligned(16))) unsigned char Xt[kTK * kStageM * 2];   // [128 k][64 m] bf16
+    __shared__ __attribute__((aligned(16))) unsigned char Ys[kStageM * kTM * 2];   // [64 token rows][128 n] bf16
+    __shared__ __attribute__((aligned(16))) unsigned char Xs[kStageM * kTK * 2];   // [64 token rows][128 k] bf16
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int N = p.N, K = p.K;
     const int nbk = K / kTK, nbn = N / kTM;
@@ -214,8 +232,9 @@ __global__ __launch_bounds__(kBwThreads, 4) void grouped_dw_kernel(DwParams p)
     if (e >= p.E) return;
     const int row0 = p.offsets[e], Me = p.offsets[e + 1] - row0;
 
-    // staging: a wavefront instruction takes one 16-byte piece (8 columns) of 64 consecutive token rows
-    const int sm = lane;             // token row of the stage
+    // staging: thread -> token rows tid / 16 and tid / 16 + 32 of the stage, 16-byte piece tid % 16 of their 128
+    // columns (16 lanes take 256 contiguous bytes of a row)
+    const int sr = tid >> 4, sc = tid & 15;
     const int wn = wave >> 1, wk = wave & 1, m32 = lane & 31, h = lane >> 5;
     f32x16 acc[2];
 #pragma unroll
@@ -225,42 +244,33 @@ __global__ __launch_bounds__(kBwThreads, 4) void grouped_dw_kernel(DwParams p)
 
     for (int m0 = 0; m0 < Me; m0 += kStageM) {
         u32x4 yv[2], xv[2];
-        const bool ok = m0 + sm < Me;
-        const int64_t yrow = row0 + m0 + sm;
-        int64_t xrow = 0;
-        if (ok) xrow = p.row_map ? p.row_map[yrow] : yrow;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const int cc = wave + 8 * u;   // piece 0..15 of the tile's 128 columns
+            const int r = sr + 32 * u;
             yv[u] = u32x4{0, 0, 0, 0};
             xv[u] = u32x4{0, 0, 0, 0};
-            if (ok) {
-                yv[u] = *(const u32x4 *)(p.dy + yrow * N + nb * kTM + cc * 8);
-                xv[u] = *(const u32x4 *)(p.x + xrow * K + kb * kTK + cc * 8);
+            if (m0 + r < Me) {   // rows past the expert's end contribute zeros
+                const int64_t yrow = row0 + m0 + r;
+                const int64_t xrow = p.row_map ? p.row_map[yrow] : yrow;
+                yv[u] = *(const u32x4 *)(p.dy + yrow * N + nb * kTM + sc * 8);
+                xv[u] = *(const u32x4 *)(p.x + xrow * K + kb * kTK + sc * 8);
             }
         }
         lds_barrier();   // the matrix phase of the previous stage is done
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const int cc = wave + 8 * u;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int r = cc * 8 + i;
-                const int off = r * (kStageM * 2) + (((sm >> 3) ^ swz_t(r)) << 4) + (sm & 7) * 2;
-                *(uint16_t *)(Yt + off) = (uint16_t)(yv[u][i >> 1] >> (16 * (i & 1)));
-                *(uint16_t *)(Xt + off) = (uint16_t)(xv[u][i >> 1] >> (16 * (i & 1)));
-            }
+            const int r = sr + 32 * u;
+            const int off = r * 256 + ((sc ^ swz_tr(r)) << 4);
+            *(u32x4 *)(Ys + off) = yv[u];
+            *(u32x4 *)(Xs + off) = xv[u];
         }
         lds_barrier();
 #pragma unroll
         for (int st = 0; st < kStageM / 16; ++st) {
-            const int ch = 2 * st + h;
-            const int n = wn * 32 + m32;
-            const bf16x8 a = *(const bf16x8 *)(Yt + n * (kStageM * 2) + ((ch ^ swz_t(n)) << 4));
+            const bf16x8 a = read_operand_tr(Ys, st * 16, wn * 32, lane);
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
-                const int k = wk * 64 + kt * 32 + m32;
-                const bf16x8 b = *(const bf16x8 *)(Xt + k * (kStageM * 2) + ((ch ^ swz_t(k)) << 4));
+                const bf16x8 b = read_operand_tr(Xs, st * 16, wk * 64 + kt * 32, lane);
                 acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[kt], 0, 0, 0);
             }
         }
