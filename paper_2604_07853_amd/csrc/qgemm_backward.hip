@@ -16,6 +16,8 @@
 // regime stay exact).  The codes go through the same exponent trick as in the forward, (q+24)/16 as an exact
 // bf16, written row by row ([n][k]) into LDS; the offset is removed at the end with the row sums of A' (fp32,
 // accumulated while A' is staged): dX = 16 * acc - 24 * rowsum.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace qarl {
@@ -50,21 +52,41 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // MFMA operand of lane `lane` (row or column l % 32, contraction elements 8 (l / 32) .. + 7) from a tile stored
-// [contraction index][128 columns] bf16 in 256-byte rows with swz_tr chunks: contraction rows kk0 .. kk0 + 15,
-// columns col0 .. col0 + 31.
-__device__ __forceinline__ bf16x8 read_operand_tr(const unsigned char *tile, int kk0, int col0, int lane)
+// [contraction index][128 columns] bf16 in 256-byte rows with swz_tr chunks: columns col0 .. col0 + 31 (col0 a
+// multiple of 32), contraction rows 16 st .. 16 st + 15.  The two addresses a lane passes are its base offsets
+// (computed once: the swizzle of row 16 st + c does not depend on st) plus 4096 st, an immediate of the read.
+struct TrBase {
+    int lo, hi;
+};
+__device__ __forceinline__ TrBase tr_base(int col0, int lane)
 {
     const int r16 = lane & 15, g = lane >> 4;
-    const int row = kk0 + 8 * (g >> 1) + (r16 >> 2);          // the row this lane ADDRESSES (second read: + 4)
+    const int row = 8 * (g >> 1) + (r16 >> 2);                // the row this lane ADDRESSES (second read: + 4)
     const int colq = col0 + 16 * (g & 1) + 4 * (r16 & 3);     // first of the four columns it addresses
-    const unsigned char *a0 = tile + row * 256 + (((colq >> 3) ^ swz_tr(row)) << 4) + (colq & 4) * 2;
-    const unsigned char *a1 = tile + (row + 4) * 256 + (((colq >> 3) ^ swz_tr(row + 4)) << 4) + (colq & 4) * 2;
+    TrBase b;
+    b.lo = row * 256 + (((colq >> 3) ^ swz_tr(row)) << 4) + (colq & 4) * 2;
+    b.hi = (row + 4) * 256 + (((colq >> 3) ^ swz_tr(row + 4)) << 4) + (colq & 4) * 2;
+    return b;
+}
+template <int ST>
+__device__ __forceinline__ bf16x8 read_operand_tr(const unsigned char *tile, const TrBase &b)
+{
     struct {
         s16x4 lo, hi;
     } v;
-    v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
-    v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a1);
+    v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(tile + b.lo + ST * 4096));
+    v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(tile + b.hi + ST * 4096));
     return __builtin_bit_cast(bf16x8, v);
+}
+
+// compile-time loop over the 16-element contraction steps of a stage
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>());
+        static_for<I + 1, N>(f);
+    }
 }
 
 __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
@@ -134,9 +156,11 @@ __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[kt][i] = 0.f;
 
-    for (int n0 = 0; n0 < N; n0 += kStageN) {
-        // global loads of the stage first, then the barrier that frees the buffers
-        u32x4 gv[4];
+    const TrBase tb[2] = {tr_base(wk * 64, lane), tr_base(wk * 64 + 32, lane)};
+    // The global loads of a stage are issued one stage ahead, right after the previous stage's operands have
+    // been written to LDS, so they travel during that stage's matrix phase.
+    u32x4 gv[4], wv;
+    auto load_stage = [&](int n0) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int m = am + 32 * u;
@@ -144,7 +168,10 @@ __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
             if (m < mrem) gv[u] = *(const u32x4 *)(p.dy + (int64_t)(row0 + m) * N + n0 + acn * 8);
         }
         const int64_t tile16 = ((int64_t)e * N + n0) / 16 + wave;
-        const u32x4 wv = *(const u32x4 *)(p.codes + (tile16 * G + g) * 256 + lane * 4);
+        wv = *(const u32x4 *)(p.codes + (tile16 * G + g) * 256 + lane * 4);
+    };
+    load_stage(0);
+    for (int n0 = 0; n0 < N; n0 += kStageN) {
         lds_barrier();   // the matrix phase of the previous stage is done (first trip: the scales are written)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -169,18 +196,19 @@ __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
             for (int j = 0; j < 4; ++j)
                 *(u32x4 *)(Bs + nl * 256 + (((bq * 4 + j) ^ swz_tr(nl)) << 4)) = __builtin_bit_cast(u32x4, unpack_int4_word(wv[j]));
         }
+        if (n0 + kStageN < N) load_stage(n0 + kStageN);
         lds_barrier();
-#pragma unroll
-        for (int st = 0; st < kStageN / 16; ++st) {
+        static_for<0, kStageN / 16>([&](auto st_c) {
+            constexpr int st = decltype(st_c)::value;
             const int ch = 2 * st + h;
             const int m = wm * 32 + m32;
             const bf16x8 a = *(const bf16x8 *)(As + m * 256 + ((ch ^ swz_a(m)) << 4));
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
-                const bf16x8 b = read_operand_tr(Bs, st * 16, wk * 64 + kt * 32, lane);
+                const bf16x8 b = read_operand_tr<st>(Bs, tb[kt]);
                 acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[kt], 0, 0, 0);
             }
-        }
+        });
     }
     // row sums of A': the 16 threads of a row sit in 16 consecutive lanes
 #pragma unroll
@@ -242,8 +270,11 @@ __global__ __launch_bounds__(kBwThreads, 4) void grouped_dw_kernel(DwParams p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[kt][i] = 0.f;
 
-    for (int m0 = 0; m0 < Me; m0 += kStageM) {
-        u32x4 yv[2], xv[2];
+    const TrBase ta = tr_base(wn * 32, lane), tb[2] = {tr_base(wk * 64, lane), tr_base(wk * 64 + 32, lane)};
+    // The global loads of a stage (row ids first, then the two tiles) are issued one stage ahead, right after the
+    // previous stage's tiles have been written to LDS, so they travel during that stage's matrix phase.
+    u32x4 yv[2], xv[2];
+    auto load_stage = [&](int m0) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int r = sr + 32 * u;
@@ -256,6 +287,9 @@ __global__ __launch_bounds__(kBwThreads, 4) void grouped_dw_kernel(DwParams p)
                 xv[u] = *(const u32x4 *)(p.x + xrow * K + kb * kTK + sc * 8);
             }
         }
+    };
+    load_stage(0);
+    for (int m0 = 0; m0 < Me; m0 += kStageM) {
         lds_barrier();   // the matrix phase of the previous stage is done
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -264,16 +298,17 @@ __global__ __launch_bounds__(kBwThreads, 4) void grouped_dw_kernel(DwParams p)
             *(u32x4 *)(Ys + off) = yv[u];
             *(u32x4 *)(Xs + off) = xv[u];
         }
+        if (m0 + kStageM < Me) load_stage(m0 + kStageM);
         lds_barrier();
-#pragma unroll
-        for (int st = 0; st < kStageM / 16; ++st) {
-            const bf16x8 a = read_operand_tr(Ys, st * 16, wn * 32, lane);
+        static_for<0, kStageM / 16>([&](auto st_c) {
+            constexpr int st = decltype(st_c)::value;
+            const bf16x8 a = read_operand_tr<st>(Ys, ta);
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
-                const bf16x8 b = read_operand_tr(Xs, st * 16, wk * 64 + kt * 32, lane);
+                const bf16x8 b = read_operand_tr<st>(Xs, tb[kt]);
                 acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[kt], 0, 0, 0);
             }
-        }
+        });
     }
     // lane (column m32 of tile kt, half h), register i -> weight row 32 wn + 8 (i / 4) + 4 h + i % 4
 #pragma unroll
