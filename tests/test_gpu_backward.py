@@ -43,9 +43,10 @@ def test_one_hot_gradient_bit_exact(q, oracle):
     assert np.array_equal(dx[:N], deq[0]) and np.array_equal(dx[N:], deq[1])
 
 
-def test_exact_integer_regime_bit_exact(q, oracle):
+@pytest.mark.parametrize("N", [128, 256])
+def test_exact_integer_regime_bit_exact(q, oracle, N):
     rng = np.random.default_rng(82)
-    E, N, K, rows = 3, 128, 256, (40, 0, 75)
+    E, K, rows = 3, 256, (40, 0, 75)
     M = sum(rows)
     qi = rng.integers(-7, 8, size=(E, N, K))
     qi[:, :, ::128] = 7
@@ -64,7 +65,8 @@ def test_exact_integer_regime_bit_exact(q, oracle):
     assert bool((dw[1] == 0).all())                                  # the expert without rows gets zeros
 
 
-@pytest.mark.parametrize("E,N,K,rows", [(3, 256, 384, (37, 0, 300)), (2, 128, 128, (1, 129)), (4, 384, 1024, (128, 256, 5, 64))])
+@pytest.mark.parametrize("E,N,K,rows", [(3, 256, 384, (37, 0, 300)), (2, 128, 128, (1, 129)), (4, 384, 1024, (128, 256, 5, 64)),
+                                        (2, 256, 512, (70, 129)), (3, 512, 256, (0, 200, 63))])   # several tiles along n and k, an expert without rows
 def test_general_data_both_gradients(q, oracle, E, N, K, rows):
     seed = 8300 + N + K
     rng = np.random.default_rng(seed)
