@@ -27,9 +27,10 @@ MFMA_FP8_PEAK_TF = 5000.0
 # HBM bytes per gate_up launch of the headline step from two counter runs (2.000 x FETCH_SIZE + 1.000 x WRITE_SIZE,
 # the factors a plain copy kernel of known size gives).  Counters cannot be read from inside this process, so the
 # figure is stored with the summary it comes from; it belongs to the 256-token workload and to the kernel as it
-# stood when that summary was taken (the gate_up launch of qgemm_stream_w4.hip has not changed since).
-GATE_UP_TRAFFIC_BYTES = 220271616
-GATE_UP_TRAFFIC_SOURCE = "profiles/qgemm_stream_decode256_hbm_traffic.txt"
+# stood when that summary was taken: 217 302 647 B read + 3 146 985 B written (an earlier measurement of the same
+# launch, profiles/qgemm_stream_decode256_hbm_traffic.txt, gave 220 271 616 B).
+GATE_UP_TRAFFIC_BYTES = 220449632
+GATE_UP_TRAFFIC_SOURCE = "profiles/qgemm_all_formats_hbm_traffic.txt"
 MIN_EVENT_LAUNCHES = 32   # gate_up launches bracketed by events, whatever --steps is
 
 
