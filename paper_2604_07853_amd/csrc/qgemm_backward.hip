@@ -160,15 +160,15 @@ __global__ __launch_bounds__(kBwThreads, 4) void qgemm_dx_kernel(DxParams p)
     // The global loads of a stage are issued one stage ahead, right after the previous stage's operands have
     // been written to LDS, so they travel during that stage's matrix phase.
     u32x4 gv[4], wv;
+    const uint16_t *gbase = p.dy + (int64_t)(row0 + am) * N + acn * 8;                      // row am of the tile; row am + 32 u: + 32 u N
+    const uint32_t *cbase = p.codes + (((int64_t)e * N / 16 + wave) * G + g) * 256 + lane * 4;   // tile of rows n0 + 16 wave ..: + (n0 / 16) G blocks
     auto load_stage = [&](int n0) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int m = am + 32 * u;
             gv[u] = u32x4{0, 0, 0, 0};
-            if (m < mrem) gv[u] = *(const u32x4 *)(p.dy + (int64_t)(row0 + m) * N + n0 + acn * 8);
+            if (am + 32 * u < mrem) gv[u] = *(const u32x4 *)(gbase + (uint32_t)(32 * u) * (uint32_t)N + n0);
         }
-        const int64_t tile16 = ((int64_t)e * N + n0) / 16 + wave;
-        wv = *(const u32x4 *)(p.codes + (tile16 * G + g) * 256 + lane * 4);
+        wv = *(const u32x4 *)(cbase + (uint32_t)(n0 / 16) * (uint32_t)(G * 256));
     };
     load_stage(0);
     for (int n0 = 0; n0 < N; n0 += kStageN) {
@@ -273,18 +273,21 @@ __global__ __launch_bounds__(kBwThreads, 4) void grouped_dw_kernel(DwParams p)
     const TrBase ta = tr_base(wn * 32, lane), tb[2] = {tr_base(wk * 64, lane), tr_base(wk * 64 + 32, lane)};
     // The global loads of a stage (row ids first, then the two tiles) are issued one stage ahead, right after the
     // previous stage's tiles have been written to LDS, so they travel during that stage's matrix phase.
+    // (addresses: one pointer per tile and one widening multiply-add per load)
     u32x4 yv[2], xv[2];
+    const uint16_t *ybase = p.dy + (int64_t)row0 * N + nb * kTM + sc * 8;
+    const uint16_t *xbase = p.x + kb * kTK + sc * 8;
+    const int32_t *mbase = p.row_map ? p.row_map + row0 : nullptr;
     auto load_stage = [&](int m0) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const int r = sr + 32 * u;
+            const int r = m0 + sr + 32 * u;
             yv[u] = u32x4{0, 0, 0, 0};
             xv[u] = u32x4{0, 0, 0, 0};
-            if (m0 + r < Me) {   // rows past the expert's end contribute zeros
-                const int64_t yrow = row0 + m0 + r;
-                const int64_t xrow = p.row_map ? p.row_map[yrow] : yrow;
-                yv[u] = *(const u32x4 *)(p.dy + yrow * N + nb * kTM + sc * 8);
-                xv[u] = *(const u32x4 *)(p.x + xrow * K + kb * kTK + sc * 8);
+            if (r < Me) {   // rows past the expert's end contribute zeros
+                const uint32_t xrow = mbase ? (uint32_t)mbase[r] : (uint32_t)(row0 + r);
+                yv[u] = *(const u32x4 *)(ybase + (uint64_t)(uint32_t)r * (uint32_t)N);
+                xv[u] = *(const u32x4 *)(xbase + (uint64_t)xrow * (uint32_t)K);
             }
         }
     };
@@ -311,15 +314,14 @@ __global__ __launch_bounds__(kBwThreads, 4) void grouped_dw_kernel(DwParams p)
         });
     }
     // lane (column m32 of tile kt, half h), register i -> weight row 32 wn + 8 (i / 4) + 4 h + i % 4
+    const int64_t obase = ((int64_t)e * N + nb * kTM + wn * 32 + 4 * h) * K + kb * kTK + wk * 64 + m32;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int64_t n = nb * kTM + wn * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+        const uint32_t orow = (uint32_t)(8 * (i >> 2) + (i & 3)) * (uint32_t)K;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
-            const int64_t col = kb * kTK + wk * 64 + kt * 32 + m32;
-            const int64_t o = ((int64_t)e * N + n) * K + col;
-            if (p.out_f32) ((float *)p.out)[o] = acc[kt][i];
-            else ((uint16_t *)p.out)[o] = f32_to_bf16_hw(acc[kt][i]);
+            if (p.out_f32) ((float *)p.out + obase)[orow + kt * 32] = acc[kt][i];
+            else ((uint16_t *)p.out + obase)[orow + kt * 32] = f32_to_bf16_hw(acc[kt][i]);
         }
     }
 }
