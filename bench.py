@@ -95,6 +95,23 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / iters  # ms
 
+    def rotate(items):
+        """A callable that returns the next of `items` at every call: GEMM launches timed on their own alternate
+        between copies of the weights, so that a tensor smaller than the 256 MB last-level cache is not served
+        from it (inside a layer the other launches evict it)."""
+        state = [0]
+
+        def nxt():
+            state[0] += 1
+            return items[state[0] % len(items)]
+        return nxt
+
+    def clone_qw(w):
+        c = q.QWeight.empty(w.fmt, w.E, w.N, w.K, dev)
+        c.codes.copy_(w.codes)
+        c.scales.copy_(w.scales)
+        return c
+
     # ---- weights: `copies` independently drawn layers, quantized by the library's own kernel
     layers = []
     masters0 = None
@@ -258,13 +275,14 @@ def main():
             ms_all = timed(lambda: lp_layer.forward(xp, lgp), 10, 2)
             r = lp_layer.routing
             Mp = Tp * TOPK
-            ms_gu_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.gu, xp, r.offsets, Mp, row_map=r.tokens,
+            next_gu, next_dn = rotate([l.gu for l in layers]), rotate([l.dn for l in layers])
+            ms_gu_p = timed(lambda: q.qarl_qgemm_grouped(next_gu(), xp, r.offsets, Mp, row_map=r.tokens,
                                                          epilogue=q.QARL_EPI_SILU_MUL, out=lp_layer.a,
-                                                         path=q.QARL_PATH_PREFILL, ws=lp_layer.ws), 10, 2)
+                                                         path=q.QARL_PATH_PREFILL, ws=lp_layer.ws), 12, 2)
             ybuf = torch.empty((Mp, H), dtype=torch.float32, device=dev)
-            ms_dn_p = timed(lambda: q.qarl_qgemm_grouped(lp_layer.dn, lp_layer.a, r.offsets, Mp, out=ybuf,
+            ms_dn_p = timed(lambda: q.qarl_qgemm_grouped(next_dn(), lp_layer.a, r.offsets, Mp, out=ybuf,
                                                          out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_PREFILL,
-                                                         ws=lp_layer.ws), 10, 2)
+                                                         ws=lp_layer.ws), 12, 2)
             del ybuf
             fl_gu, fl_dn = 2 * Mp * 2 * I * H, 2 * Mp * H * I
             extra["prefill_w4a16_16384tok_zipf"] = {
@@ -360,20 +378,25 @@ def main():
                 l8 = q.MoELayer(qgu8, qdn8, T8, TOPK, path, dev)
                 ms8 = timed(lambda: l8.forward(x8, lg8), 20, 3)
                 r8, M8 = l8.routing, T8 * TOPK
+                def copies_of(w):   # enough copies that their codes exceed three times the last-level cache
+                    n = max(2, -(-768 * 2 ** 20 // (w.codes.numel() * w.codes.element_size())))
+                    return [w] + [clone_qw(w) for _ in range(n - 1)]
+                gu_set, dn_set = copies_of(qgu8), copies_of(qdn8)
+                next_gu, next_dn = rotate(gu_set), rotate(dn_set)
                 if l8.routed:   # decode: the GEMMs read the router's ids and quantize the rows they gather
-                    ms8_gu = timed(lambda: q.qarl_qgemm_routed(qgu8, x8, r8.ids, T8, TOPK, True, epilogue=q.QARL_EPI_SILU_MUL,
+                    ms8_gu = timed(lambda: q.qarl_qgemm_routed(next_gu(), x8, r8.ids, T8, TOPK, True, epilogue=q.QARL_EPI_SILU_MUL,
                                                                out=l8.a, ws=l8.ws), 20, 3)
                     y8 = torch.empty((M8, H), dtype=torch.float32, device=dev)
-                    ms8_dn = timed(lambda: q.qarl_qgemm_routed(qdn8, l8.a, r8.ids, T8, TOPK, False, out=y8,
+                    ms8_dn = timed(lambda: q.qarl_qgemm_routed(next_dn(), l8.a, r8.ids, T8, TOPK, False, out=y8,
                                                                out_dtype=q.QARL_OUT_F32, ws=l8.ws), 20, 3)
                 else:
-                    ms8_gu = timed(lambda: q.qarl_qgemm_grouped(qgu8, l8.xq, r8.offsets, M8, row_map=r8.tokens, x_scales=l8.sx,
+                    ms8_gu = timed(lambda: q.qarl_qgemm_grouped(next_gu(), l8.xq, r8.offsets, M8, row_map=r8.tokens, x_scales=l8.sx,
                                                                 epilogue=q.QARL_EPI_SILU_MUL, out=l8.a, path=path,
                                                                 ws=l8.ws), 20, 3)
                     y8 = torch.empty((M8, H), dtype=torch.float32, device=dev)
-                    ms8_dn = timed(lambda: q.qarl_qgemm_grouped(qdn8, l8.aq, r8.offsets, M8, x_scales=l8.sa, out=y8,
+                    ms8_dn = timed(lambda: q.qarl_qgemm_grouped(next_dn(), l8.aq, r8.offsets, M8, x_scales=l8.sa, out=y8,
                                                                 out_dtype=q.QARL_OUT_F32, path=path, ws=l8.ws), 20, 3)
-                del y8
+                del y8, gu_set, dn_set, next_gu, next_dn
                 f8 = synth.flops_moe(T8)
                 extra["%s_%s_%dtok" % (fname, tag, T8)] = {
                     "layer_ms": round(ms8, 4), "gate_up_ms": round(ms8_gu, 4), "down_ms": round(ms8_dn, 4),

@@ -407,7 +407,7 @@ __global__ __launch_bounds__(kFThreads, 2) void qgemm_tile_fp8_kernel(Tile8Param
                     if (orow_r >= 0 && tile_ok) {
                         unsigned char *dstp = (unsigned char *)p.out + (uint64_t)(uint32_t)orow_r * rstride;
                         if (p.out_f32) {
-                            *(f32x4 *)(dstp + col * 4) = v4;
+                            __builtin_nontemporal_store(v4, (f32x4 *)(dstp + col * 4));   // fp32 rows for the combine: written once, read once by another kernel
                         } else {
                             u32x2 o;
                             o[0] = (uint32_t)f32_to_bf16_hw(v4[0]) | ((uint32_t)f32_to_bf16_hw(v4[1]) << 16);
