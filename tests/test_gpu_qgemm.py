@@ -26,7 +26,8 @@ TOL_F32_FP8 = 1e-3
 MAX_FLIPS_FP8 = 0.06
 # FP8 layer end to end against the oracle's own chain: one moved e4m3 code of the intermediate changes one of I
 # products by up to 2^-3 of its size, a moved row scale a few per cent of them; after the down projection and the
-# combine that is a few 1e-3 of the output's rms on the rows it hits (derivation in the design doc, section 4).
+# combine that is a few 1e-3 of the output's rms on the rows it hits; a row whose largest element moved gets
+# another scale and a few per cent new codes, which is worth up to 1e-1 of the rms on that token.
 FP8_E2E_MAX = 5e-2
 FP8_E2E_MAX_SCALE = 0.2   # tokens with a pair-row whose scale moved by one bf16 step of its largest element
 
