@@ -57,8 +57,12 @@ def test_fp4_quantizer_bit_exact(q, oracle):
 
 
 @pytest.mark.parametrize("fmt", ["fp4", "w4a8"])
-@pytest.mark.parametrize("E,N,K,rows", [(3, 96, 256, (37, 0, 5)), (2, 288, 512, (300, 129)), (1, 32, 256, (1,))])
+@pytest.mark.parametrize("E,N,K,rows", [(3, 96, 256, (37, 0, 5)), (2, 288, 512, (300, 129)), (1, 32, 256, (1,)),
+                                        (2, 96, 128, (40, 3)),          # a single 128-k stage
+                                        (2, 544, 384, (130, 260))])     # three stages, three column blocks, ragged token tiles
 def test_gemm_both_paths(q, oracle, fmt, E, N, K, rows):
+    if fmt == "w4a8" and K % 256:
+        pytest.skip("the int4 decode kernel takes K % 256 == 0")
     seed = 2100 + N + K
     w = synth.normal_bf16((E, N, K), 0.02, seed=seed)
     M = int(sum(rows))
