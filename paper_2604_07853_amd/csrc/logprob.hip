@@ -15,6 +15,7 @@
 // instruction, coalesced) and the operand reads (32 rows, one chunk) are both free of bank conflicts.
 // Operand reads run one 16-k slice ahead of the MFMAs, across the stage barrier as well.
 #include "common.hpp"
+#include <type_traits>
 
 namespace qarl {
 
@@ -67,13 +68,15 @@ __global__ __launch_bounds__(kLThreads, 2) void lmhead_lse_kernel(LogprobParams 
     }
     const unsigned char *wbase = (const unsigned char *)p.w + (int64_t)v0 * H * 2;
     const unsigned char *hbase = (const unsigned char *)p.h + (int64_t)t0 * H * 2;
-    auto copy_stage = [&](int ks, int buf) {
+    // copy i of the wavefront's eight per stage (four W row groups, then four h row groups)
+    auto copy_one = [&](int ks, int buf, int i) {
         unsigned char *dst = smem + buf * kLStageB + wave * 32 * kLRowB;
-        const unsigned char *ws = wbase + (int64_t)ks * kLRowB, *hs = hbase + (int64_t)ks * kLRowB;
+        if (i < 4) copy16_to_lds(wbase + (int64_t)ks * kLRowB + woff[i], dst + i * 8 * kLRowB);
+        else copy16_to_lds(hbase + (int64_t)ks * kLRowB + hoff[i - 4], dst + kLTileB + (i - 4) * 8 * kLRowB);
+    };
+    auto copy_stage = [&](int ks, int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) copy16_to_lds(ws + woff[i], dst + i * 8 * kLRowB);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) copy16_to_lds(hs + hoff[i], dst + kLTileB + i * 8 * kLRowB);
+        for (int i = 0; i < 8; ++i) copy_one(ks, buf, i);
     };
 
     // ---- operand reads: lane (c,h) takes row c of a 32-row tile, k in [16 j + 8 h, +8) = chunk 2j + h
@@ -84,14 +87,6 @@ __global__ __launch_bounds__(kLThreads, 2) void lmhead_lse_kernel(LogprobParams 
     struct Frags {
         bf16x8 a[4], b[2];
     };
-    auto read_frags = [&](Frags &f, int buf, int j) {
-        const unsigned char *base = smem + buf * kLStageB + aoff[j];
-#pragma unroll
-        for (int ms = 0; ms < 4; ++ms) f.a[ms] = *(const bf16x8 *)(base + a_wave + ms * 32 * kLRowB);
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) f.b[nt] = *(const bf16x8 *)(base + b_wave + nt * 32 * kLRowB);
-    };
-
     f32x16 acc[4][2];
 #pragma unroll
     for (int ms = 0; ms < 4; ++ms)
@@ -106,17 +101,26 @@ __global__ __launch_bounds__(kLThreads, 2) void lmhead_lse_kernel(LogprobParams 
             for (int nt = 0; nt < 2; ++nt)
                 acc[ms][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ms], f.b[nt], acc[ms][nt], 0, 0, 0);
     };
-    // Issue order of a slice: one MFMA, then the six operand reads of the next slice one by one between the
-    // next six MFMAs (an LDS read every 32 cycles instead of six at once; 3 % faster than all six behind
-    // the first MFMA), then the last MFMA.
-    auto interleave = [&]() {
+    // Slice j of a stage, in a fixed issue order: the eight MFMAs on `cur`; behind each of the first six, one of the
+    // six operand reads of `nxt` (an LDS read every 32 cycles instead of six at once: 3 % faster than all six
+    // behind the first MFMA); in slices 0 and 1, behind every second MFMA, one of the next stage's eight copies.
+    // Measured at 16384 x 151936 x 2048: all eight at the top of the stage 9.0 ms (a wavefront that waits for room
+    // in the memory pipeline is kept from its matrix instructions), two per slice 8.45, three-three-two 8.07,
+    // four-four 7.86 (the later a copy goes out, the less of its latency the rest of the stage covers), one behind
+    // each MFMA of slice 0 7.99.
+    auto slice = [&](const Frags &cur, Frags &nxt, int ks, int j, auto more_t) {
+        const int buf = ks & 1;
+        const unsigned char *base = smem + buf * kLStageB + aoff[j];
 #pragma unroll
-        for (int i = 0; i < 6; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        for (int i = 0; i < 8; ++i) {
+            const int ms = i >> 1, nt = i & 1;
+            acc[ms][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[ms], cur.b[nt], acc[ms][nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i < 4) nxt.a[i] = *(const bf16x8 *)(base + a_wave + i * 32 * kLRowB);
+            else if (i < 6) nxt.b[i - 4] = *(const bf16x8 *)(base + b_wave + (i - 4) * 32 * kLRowB);
+            if (decltype(more_t)::value && j < 2 && (i & 1)) copy_one(ks + 1, buf ^ 1, 4 * j + (i >> 1));
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        __builtin_amdgcn_sched_barrier(0);
     };
     auto stage_barrier = [&]() {
         // own copies landed, own operand reads done; then everybody's
@@ -134,24 +138,17 @@ __global__ __launch_bounds__(kLThreads, 2) void lmhead_lse_kernel(LogprobParams 
     for (int i = 0; i < 2; ++i) last.b[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     copy_stage(0, 0);
     stage_barrier();
-    for (int ks = 0; ks < stages; ++ks) {
-        const int buf = ks & 1;
-        if (ks + 1 < stages) copy_stage(ks + 1, buf ^ 1);
-        read_frags(f0, buf, 0);
-        mfma8(last);
-        interleave();
-        read_frags(f1, buf, 1);
-        mfma8(f0);
-        interleave();
-        read_frags(f2, buf, 2);
-        mfma8(f1);
-        interleave();
-        read_frags(f3, buf, 3);
-        mfma8(f2);
-        interleave();
+    // One stage; the last has no copies to issue, so the loop's last trip is peeled.
+    auto stage = [&](int ks, auto more_t) {
+        slice(last, f0, ks, 0, more_t);
+        slice(f0, f1, ks, 1, more_t);
+        slice(f1, f2, ks, 2, more_t);
+        slice(f2, f3, ks, 3, more_t);
         stage_barrier();
         last = f3;
-    }
+    };
+    for (int ks = 0; ks + 1 < stages; ++ks) stage(ks, std::true_type{});
+    stage(stages - 1, std::false_type{});
     mfma8(last);
 
     // ---- per token: max and sum of exp over this wavefront's 128 vocabulary rows.
