@@ -88,6 +88,60 @@ def test_gemm_both_paths(q, oracle, fmt, E, N, K, rows):
         assert e <= tol, (fmt, path, e)
 
 
+# Experts with several token tiles each on the tiled path: ragged last tiles, empty experts, one / three (odd) / eight
+# 128-k stages, a last column block that is not full, and all three epilogues on the same product.
+_TALL_SHAPES = [(2, 544, 384, (517, 390)), (1, 96, 128, (400,)), (3, 288, 1024, (0, 1300, 0)), (2, 64, 256, (256, 512))]
+
+
+def _quantized(q, oracle, fmt, w):
+    if fmt == "fp4":
+        wq, sw = oracle.quantize_fp4_rows(np_bits(w))
+        return wq, sw, oracle.qgemm_fp4w, q.qarl_quantize_weights(w.cuda(), q.QARL_FP4_E2M1_CH)
+    wq, sw = oracle.quantize_fp8_rows(np_bits(w))
+    return wq, sw, oracle.qgemm_fp8, q.qarl_quantize_weights(w.cuda(), q.QARL_FP8_E4M3_CH)
+
+
+@pytest.mark.parametrize("fmt,E,N,K,rows", [(f,) + sh for f in ("fp8", "fp4") for sh in _TALL_SHAPES])
+def test_tiled_path_several_tiles_per_expert(q, oracle, fmt, E, N, K, rows):
+    seed = 2500 + N + K
+    w = synth.normal_bf16((E, N, K), 0.02, seed=seed)
+    M = int(sum(rows))
+    x = synth.normal_bf16((M, K), 1.0, seed=seed + 1)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    rm = np.random.default_rng(seed).permutation(M).astype(np.int32)
+    xq_ref, sx_ref = oracle.quantize_fp8_rows(np_bits(x))
+    xq, sx = q.qarl_quantize_rows_fp8(x.cuda())
+    wq, sw, gemm, qw = _quantized(q, oracle, fmt, w)
+    ref = gemm(xq_ref, sx_ref, wq, sw, off, rm)
+    y = q.qarl_qgemm_grouped(qw, xq, _i32(off), M, row_map=_i32(rm), x_scales=sx, out_dtype=q.QARL_OUT_F32,
+                             path=q.QARL_PATH_PREFILL)
+    assert norm_err(y.cpu().numpy(), ref) <= TOL_F32_FP8
+    yb = q.qarl_qgemm_grouped(qw, xq, _i32(off), M, row_map=_i32(rm), x_scales=sx, path=q.QARL_PATH_PREFILL)
+    assert np.array_equal(np_bits(yb), np_bits(y.to(torch.bfloat16)))        # the 16-bit output is the rounded fp32 one
+    # gate rows then up rows: the SiLU-gated epilogue on the same product
+    a = q.qarl_qgemm_grouped(qw, xq, _i32(off), M, row_map=_i32(rm), x_scales=sx, epilogue=q.QARL_EPI_SILU_MUL,
+                             path=q.QARL_PATH_PREFILL)
+    a_bits, a_ref = oracle.silu_mul(ref)
+    assert norm_err_bf16(a.float().cpu().numpy(), a_ref) <= TOL_BF16
+    assert flip_fraction(np_bits(a), a_bits) <= MAX_FLIPS_FP8
+
+
+@pytest.mark.parametrize("fmt", ["fp8", "fp4"])
+def test_one_hot_probe_four_token_tiles(q, oracle, fmt):
+    """512 one-hot rows (448 e_k, scale 1) of one expert, 320 weight rows: the tiled kernel returns 448 times the
+    dequantized weight bit for bit, i.e. every k of every stage meets its own weight element in every wavefront's tiles
+    of every token tile and column block."""
+    K, N = 512, 320
+    w = synth.normal_bf16((1, N, K), 0.02, seed=63)
+    x = (torch.eye(K) * 448).to(torch.bfloat16).cuda()
+    xq, sx = q.qarl_quantize_rows_fp8(x)
+    wq, sw, _, qw = _quantized(q, oracle, fmt, w)
+    dec = oracle.e2m1_decode(wq[0]) if fmt == "fp4" else oracle.e4m3_decode(wq[0])
+    want = (dec * 448.0 * sw[0][:, None].astype(np.float64)).T
+    y = q.qarl_qgemm_grouped(qw, xq, _i32([0, K]), K, x_scales=sx, out_dtype=q.QARL_OUT_F32, path=q.QARL_PATH_PREFILL)
+    assert np.array_equal(y.cpu().numpy().astype(np.float64), want.astype(np.float32).astype(np.float64))
+
+
 @pytest.mark.parametrize("fmt", ["fp4", "w4a8"])
 def test_one_hot_probe_bit_exact(q, oracle, fmt):
     """x rows = 448 e_k with scale 1: the output is 448 times the dequantized weight, no accumulation, both paths."""
