@@ -123,3 +123,75 @@ def test_routed_random_shape(q, oracle, case):
     a_bits, a_ref = oracle.silu_mul(ref)
     assert norm_err_bf16(a.float().cpu().numpy()[pairs], a_ref) <= TOL_BF16, what
     assert flip_fraction(np_bits(a)[pairs], a_bits) <= MAX_FLIPS, what
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_quantizers_router_logprob_backward_random_shape(q, oracle, case):
+    """The other entry points on random sizes: the three weight quantizers and the row quantizer (bit-exact, weight
+    magnitudes from 1e-3 to 300), router + grouping (bit-exact, weights 1e-6), the fused log-prob (1e-4) and both
+    gradients of the straight-through backward (the bars of test_gpu_backward)."""
+    from gpu_util import unblock_int4
+    rng = np.random.default_rng(48000 + case)
+    E, N, K = int(rng.integers(1, 5)), 32 * int(rng.integers(1, 9)), 128 * int(rng.integers(1, 33))
+    std = float(rng.choice([1e-3, 0.02, 1.0, 300.0]))
+    w = synth.normal_bf16((E, N, K), std, seed=48100 + case)
+    c, s = oracle.quantize_int4(np_bits(w))
+    qw = q.qarl_quantize_weights(w.cuda(), q.QARL_W4A16_G128)
+    assert np.array_equal(qw.scales.cpu().view(torch.int16).numpy().view(np.uint16), s), (E, N, K, std)
+    assert np.array_equal(unblock_int4(qw.codes, E, N, K), c), (E, N, K, std)
+    c, s = oracle.quantize_fp8_rows(np_bits(w))
+    qw = q.qarl_quantize_weights(w.cuda(), q.QARL_FP8_E4M3_CH)
+    assert np.array_equal(qw.scales.cpu().numpy(), s) and np.array_equal(qw.codes.cpu().numpy(), c), (E, N, K, std)
+    c, s = oracle.quantize_fp4_rows(np_bits(w))
+    qw = q.qarl_quantize_weights(w.cuda(), q.QARL_FP4_E2M1_CH)
+    assert np.array_equal(qw.scales.cpu().numpy(), s), (E, N, K, std)
+    want = np.zeros((E, N, K // 8), dtype=np.uint32)           # the oracle's one code per byte -> nibble i of a word
+    for i in range(8):
+        want |= c.reshape(E, N, K // 8, 8)[..., i].astype(np.uint32) << np.uint32(4 * i)
+    assert np.array_equal(q.qarl_codes_to_canonical(qw).cpu().numpy().view(np.uint32).reshape(want.shape), want), (E, N, K, std)
+    rows = int(rng.integers(1, 300))
+    x = synth.normal_bf16((rows, K), std, seed=48200 + case)
+    c, s = oracle.quantize_fp8_rows(np_bits(x))
+    gc, gs = q.qarl_quantize_rows_fp8(x.cuda())
+    assert np.array_equal(gs.cpu().numpy(), s) and np.array_equal(gc.cpu().numpy(), c), (rows, K, std)
+
+    T, Er, topk = int(rng.integers(1, 3000)), int(rng.choice([64, 128, 192, 256])), int(rng.integers(1, 17))
+    lg = synth.router_logits(T, Er, seed=48300 + case, zipf_s=float(rng.choice([0.0, 1.1, 1.5])))
+    ids, wts = oracle.route(np_bits(lg), topk)
+    counts, offsets, pairs = oracle.group(ids, Er)
+    r = q.qarl_moe_route(lg.cuda(), topk)
+    what = (T, Er, topk)
+    assert np.array_equal(r.ids.cpu().numpy(), ids) and np.array_equal(r.counts.cpu().numpy(), counts), what
+    assert np.array_equal(r.offsets.cpu().numpy(), offsets) and np.array_equal(r.pairs.cpu().numpy(), pairs), what
+    assert np.array_equal(r.tokens.cpu().numpy(), pairs // topk), what
+    assert np.allclose(r.w.cpu().numpy().astype(np.float64), wts, rtol=1e-6, atol=0), what
+
+    Tl, H, V = int(rng.integers(1, 400)), 64 * int(rng.integers(1, 9)), int(rng.integers(1, 3000))
+    inv_t = float(rng.choice([1.0, 0.5, 3.0]))
+    h = synth.normal_bf16((Tl, H), 1.0, seed=48400 + case)
+    wl = synth.normal_bf16((V, H), 0.3, seed=48500 + case)
+    tg = synth.targets(Tl, V, seed=48600 + case)
+    ref = oracle.token_logprob(np_bits(h), np_bits(wl), tg.numpy(), inv_t)
+    got = q.qarl_token_logprob(h.cuda(), wl.cuda(), tg.cuda(), inv_t)["logprob"]
+    assert np.abs(got.cpu().numpy().astype(np.float64) - ref).max() <= 1e-4 * max(1.0, np.abs(ref).max() / 10), (Tl, H, V, inv_t)
+    assert torch.equal(got, q.qarl_token_logprob(h.cuda(), wl.cuda(), tg.cuda(), inv_t)["logprob"]), (Tl, H, V, inv_t)
+
+    Eb, Nb, Kb = int(rng.integers(1, 5)), 128 * int(rng.integers(1, 5)), 128 * int(rng.integers(1, 9))
+    rws = (rng.integers(0, 200, size=Eb) * (rng.random(Eb) < 0.75)).astype(np.int64)
+    if rws.sum() == 0:
+        rws[0] = 5
+    M = int(rws.sum())
+    wq = synth.normal_bf16((Eb, Nb, Kb), 0.02, seed=48700 + case)
+    dy = synth.normal_bf16((M, Nb), 1.0, seed=48800 + case)
+    xb = synth.normal_bf16((M + 3, Kb), 1.0, seed=48900 + case)
+    off = np.concatenate([[0], np.cumsum(rws)]).astype(np.int32)
+    rm = rng.permutation(M + 3)[:M].astype(np.int32)
+    codes, scales = oracle.quantize_int4(np_bits(wq))
+    qwb = q.qarl_quantize_weights(wq.cuda())
+    what = (Eb, Nb, Kb, rws.tolist())
+    dx = q.qarl_qgemm_grouped_dx(qwb, dy.cuda(), _i32(off), M, out_dtype=q.QARL_OUT_F32)
+    dw = q.qarl_grouped_dw(dy.cuda(), xb.cuda(), _i32(off), Eb, row_map=_i32(rm), out_dtype=q.QARL_OUT_F32)
+    assert norm_err(dx.cpu().numpy(), oracle.qgemm_w4a16_dx(np_bits(dy), codes, scales, off)) <= 1e-2, what
+    assert norm_err(dw.cpu().numpy(), oracle.grouped_dw(np_bits(dy), np_bits(xb), off, Eb, rm)) <= TOL["w4a16"], what
+    assert torch.equal(dx, q.qarl_qgemm_grouped_dx(qwb, dy.cuda(), _i32(off), M, out_dtype=q.QARL_OUT_F32)), what
+    assert torch.equal(dw, q.qarl_grouped_dw(dy.cuda(), xb.cuda(), _i32(off), Eb, row_map=_i32(rm), out_dtype=q.QARL_OUT_F32)), what
