@@ -14,11 +14,24 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
     if (idx >= (int64_t)T * n4) return;
     const int t = (int)(idx / n4), c4 = (int)(idx % n4);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int j = 0; j < topk; ++j) {
-        const float wj = w[(int64_t)t * topk + j];
-        const f32x4 v = *(const f32x4 *)(y + ((int64_t)t * topk + j) * N + c4 * 4);
+    // eight slots' loads go out together (the rows are read once: nontemporal), the sum stays in slot order
+    const float *yt = y + (int64_t)t * topk * N + c4 * 4;
+    const float *wt = w + (int64_t)t * topk;
+    for (int j0 = 0; j0 < topk; j0 += 8) {
+        f32x4 v[8];
+        float wj[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = fmaf(wj, v[i], acc[i]);
+        for (int j = 0; j < 8; ++j) {
+            const int jj = min(j0 + j, topk - 1);
+            v[j] = __builtin_nontemporal_load((const f32x4 *)(yt + (int64_t)jj * N));
+            wj[j] = wt[jj];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (j0 + j < topk) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] = fmaf(wj[j], v[j][i], acc[i]);
+            }
     }
     if (out_f32) {
         *(f32x4 *)((float *)out + (int64_t)t * N + c4 * 4) = acc;

@@ -126,6 +126,70 @@ int launch_quantize_int4(const void *w, int64_t rows, int K, void *codes, void *
 // pass and the conversion pass, longer rows are read a second time (a cache hit).
 constexpr int kF8Threads = 256;
 
+// Chunk c (8 elements, 16 bytes of bf16) of a row -> its codes: 8 bytes of e4m3, or 4 bytes of e2m1.
+template <bool FP4>
+__device__ __forceinline__ void store_codes_bf16x8(uint8_t *codes, int64_t row, int K, int c, const RowScale &rs, float s, const u32x4 v)
+{
+    if (FP4) {
+        uint32_t w = 0;
+        if (s != 0.f) {
+            // v_cvt_scalef32_pk_fp4_f32 with scale 1 rounds to the nearest e2m1 value, ties to the even code,
+            // saturating at 6, and puts its two results into one byte (first source in the low nibble): byte b
+            // takes elements b and 4 + b.  Checked against a software encoder (comparisons with the seven rounding
+            // boundaries) on every boundary, its two neighbours, zeros of both signs, tiny and huge values and 2^16
+            // random ones on gfx950: identical.
+            float t[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                t[2 * i] = rs.div(__uint_as_float(v[i] << 16));
+                t[2 * i + 1] = rs.div(__uint_as_float(v[i] & 0xffff0000u));
+            }
+            w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[0], t[4], 1.0f, 0);
+            w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[1], t[5], 1.0f, 1);
+            w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[2], t[6], 1.0f, 2);
+            w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[3], t[7], 1.0f, 3);
+        }
+        ((uint32_t *)(codes + row * (K / 2)))[c] = w;   // e2m1: 4 bytes per 8 elements
+        return;
+    }
+    ((u32x2 *)(codes + row * K))[c] = e4m3_quantize_bf16x8(rs, v);   // e4m3: 8 bytes per 8 elements
+}
+
+// Rows of at most 1024 elements (the intermediate of the MoE layer has 768): a wavefront takes four rows and requests
+// all of them before it reduces the first, so that it has 3-8 KB in flight instead of 1.5-2; same arithmetic per row
+// as the kernel below (identical bytes).
+template <bool FP4>
+__global__ __launch_bounds__(kF8Threads) void quantize_fp8_short_rows_kernel(const uint16_t *__restrict__ x, int64_t rows, int K,
+                                                                             uint8_t *__restrict__ codes, float *__restrict__ scales)
+{
+    constexpr int kRowsPerWave = 4;
+    const int lane = threadIdx.x & 63;
+    const int64_t row0 = ((int64_t)blockIdx.x * (kF8Threads / 64) + (threadIdx.x >> 6)) * kRowsPerWave;
+    const int n16 = K / 8;   // <= 128
+    u32x4 held[kRowsPerWave][2];
+#pragma unroll
+    for (int r = 0; r < kRowsPerWave; ++r) {
+        const u32x4 *xr = (const u32x4 *)(x + min(row0 + r, rows - 1) * K);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            held[r][u] = u32x4{0, 0, 0, 0};
+            if (lane + 64 * u < n16) held[r][u] = xr[lane + 64 * u];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kRowsPerWave; ++r) {
+        const int64_t row = row0 + r;
+        if (row >= rows) break;
+        const float am = wave_max(absmax_bf16x8(held[r][1], absmax_bf16x8(held[r][0], 0.f)));
+        const float s = am / (FP4 ? 6.0f : 448.0f);
+        if (lane == 0) scales[row] = s;
+        const RowScale rs(s);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            if (lane + 64 * u < n16) store_codes_bf16x8<FP4>(codes, row, K, lane + 64 * u, rs, s, held[r][u]);
+    }
+}
+
 template <bool FP4>
 __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uint16_t *__restrict__ x,
                                                                        int64_t rows, int K,
@@ -159,33 +223,8 @@ __global__ __launch_bounds__(kF8Threads) void quantize_fp8_rows_kernel(const uin
     am = wave_max(am);
     const float s = am / (FP4 ? 6.0f : 448.0f);
     if (lane == 0) scales[row] = s;
-    u32x2 *cr = (u32x2 *)(codes + row * K);           // e4m3: 8 bytes per 8 elements
-    uint32_t *cr4 = (uint32_t *)(codes + row * (K / 2));  // e2m1: 4 bytes per 8 elements
     const RowScale rs(s);   // x / s, correctly rounded, from one divide per row
-    auto convert = [&](const u32x4 v, int c) {
-        if (FP4) {
-            uint32_t w = 0;
-            if (s != 0.f) {
-                // v_cvt_scalef32_pk_fp4_f32 with scale 1 rounds to the nearest e2m1 value, ties to the even code,
-                // saturating at 6, and puts its two results into one byte (first source in the low nibble): byte b
-                // takes elements b and 4 + b.  Checked against a software encoder (comparisons with the seven rounding boundaries) on every boundary, its two
-                // neighbours, zeros of both signs, tiny and huge values and 2^16 random ones on gfx950: identical.
-                float t[8];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    t[2 * i] = rs.div(__uint_as_float(v[i] << 16));
-                    t[2 * i + 1] = rs.div(__uint_as_float(v[i] & 0xffff0000u));
-                }
-                w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[0], t[4], 1.0f, 0);
-                w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[1], t[5], 1.0f, 1);
-                w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[2], t[6], 1.0f, 2);
-                w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, t[3], t[7], 1.0f, 3);
-            }
-            cr4[c] = w;
-            return;
-        }
-        cr[c] = e4m3_quantize_bf16x8(rs, v);
-    };
+    auto convert = [&](const u32x4 v, int c) { store_codes_bf16x8<FP4>(codes, row, K, c, rs, s, v); };
     if (keep) {
 #pragma unroll
         for (int u = 0; u < kKeep; ++u)
@@ -204,6 +243,12 @@ int launch_quantize_fp8_rows(const void *x, int64_t rows, int K, void *codes, fl
         set_error("quantize_fp8: %lld blocks exceed the grid limit", (long long)blocks);
         return QARL_ERR_UNSUPPORTED;
     }
+    if (K <= 1024) {   // short rows: four per wavefront
+        const int64_t b4 = (blocks + 3) / 4;
+        quantize_fp8_short_rows_kernel<false><<<dim3((unsigned)b4), dim3(kF8Threads), 0, s>>>((const uint16_t *)x, rows, K,
+                                                                                           (uint8_t *)codes, scales);
+        return check_hip(hipGetLastError(), "quantize_fp8_short_rows_kernel");
+    }
     quantize_fp8_rows_kernel<false><<<dim3((unsigned)blocks), dim3(kF8Threads), 0, s>>>(
         (const uint16_t *)x, rows, K, (uint8_t *)codes, scales);
     return check_hip(hipGetLastError(), "quantize_fp8_rows_kernel");
@@ -217,6 +262,12 @@ int launch_quantize_fp4_rows(const void *x, int64_t rows, int K, void *codes, fl
     if (blocks > 0x7fffffffLL) {
         set_error("quantize_fp4: %lld blocks exceed the grid limit", (long long)blocks);
         return QARL_ERR_UNSUPPORTED;
+    }
+    if (K <= 1024) {   // short rows: four per wavefront
+        const int64_t b4 = (blocks + 3) / 4;
+        quantize_fp8_short_rows_kernel<true><<<dim3((unsigned)b4), dim3(kF8Threads), 0, s>>>((const uint16_t *)x, rows, K,
+                                                                                           (uint8_t *)codes, scales);
+        return check_hip(hipGetLastError(), "quantize_fp4_short_rows_kernel");
     }
     quantize_fp8_rows_kernel<true><<<dim3((unsigned)blocks), dim3(kF8Threads), 0, s>>>(
         (const uint16_t *)x, rows, K, (uint8_t *)codes, scales);
