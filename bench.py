@@ -334,7 +334,7 @@ def main():
 
         if on("backward"):
             # straight-through backward of the gate_up projection at the training-forward shape (16 384 tokens, Zipf):
-            # dX = dY What (128 x 128 tiles, 16-bit operands) and dW = dY^T X
+            # dX = dY What (128 x 128 tiles, 16-bit operands) and dW = dY^T X (256 x 256 tiles)
             Tb = 16384
             Mb = Tb * TOPK
             lgb = synth.router_logits(Tb, E, seed=31, device=dev, zipf_s=1.1)

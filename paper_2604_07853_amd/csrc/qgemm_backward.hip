@@ -326,6 +326,227 @@ __global__ __launch_bounds__(kBwThreads, 4) void grouped_dw_kernel(DwParams p)
     }
 }
 
+
+// ---- dW on 256 x 256 tiles: the structure of the LM head kernel (logprob.hip) with the token index as the
+// contraction.  A stage holds 64 token rows of both operands as they are stored, Ys [64][256 n] and Xs [64][256 k]
+// (512-byte rows, 64 KiB per stage, two stages), filled by asynchronous global -> LDS copies: a wavefront instruction
+// moves two rows; chunk q (16 bytes) of row r sits at position q ^ ((r & 3) << 2) of the row, so that the four rows
+// a transposing read touches at once lie in different quarters of the 256 bytes the LDS serves per clock.  Rows past
+// the expert's end are copied from a row of zeros.  Eight wavefronts of 128 n x 64 k (4 x 2 MFMA tiles, 128
+// accumulator registers); the twelve transposing reads of a 16-token slice go out one pair behind each of the first
+// six MFMAs of the slice before, the eight copies of the next stage one behind every second MFMA of the first two
+// slices, the last slice's MFMAs run behind the stage barrier.  The x rows are gathered through row_map; the ids
+// are the same for all lanes of a wavefront and are read with scalar loads (vector loads would share the counter
+// the copies are waited on with) one stage before they are turned into addresses.
+constexpr int kDwWTile = 256;                       // n rows and k columns per workgroup
+constexpr int kDwWRowB = kDwWTile * 2;              // bytes of an LDS row
+constexpr int kDwWTileB = kStageM * kDwWRowB;       // one operand tile of a stage: 32 KiB
+constexpr int kDwWStageB = 2 * kDwWTileB;           // Ys, then Xs
+__device__ __attribute__((aligned(256))) const unsigned char kDwZeroRow[kDwWRowB] = {0};
+
+__device__ __forceinline__ TrBase tr_base_512(int col0, int lane)
+{
+    const int r16 = lane & 15, g = lane >> 4;
+    const int row = 8 * (g >> 1) + (r16 >> 2);                // the row this lane ADDRESSES (second read: + 4)
+    const int colq = col0 + 16 * (g & 1) + 4 * (r16 & 3);     // first of the four columns it addresses
+    TrBase b;
+    b.lo = row * kDwWRowB + (((colq >> 3) ^ ((row & 3) << 2)) << 4) + (colq & 4) * 2;
+    b.hi = b.lo + 4 * kDwWRowB;                               // row + 4: same row & 3, same swizzle
+    return b;
+}
+
+__global__ __launch_bounds__(kBwThreads, 2) void grouped_dw_wide_kernel(DwParams p, const int32_t *__restrict__ row_map)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave >> 2, wk = wave & 3;   // 128 n x 64 k per wavefront
+    const int m32 = lane & 31, h = lane >> 5;
+    const int N = p.N, K = p.K;
+    const int nbn = N / kDwWTile, nbk = K / kDwWTile, tiles = nbn * nbk;
+    // Every expert's tiles are spread over all eight XCDs (consecutive workgroup ids go round-robin over them), so a
+    // skewed router loads the XCDs alike; where the tile grid allows it an XCD takes half of the n blocks and a
+    // quarter of the k blocks of every expert, i.e. its L2 fetches a fifth of the expert's operand bytes, not all.
+    int e, nb, kb;
+    if (nbn % 2 == 0 && nbk % 4 == 0) {
+        const int xcd = blockIdx.x % 8, idx = blockIdx.x / 8, per = tiles / 8, hn = nbn / 2;
+        e = idx / per;
+        nb = (xcd & 1) * hn + (idx % per) % hn;
+        kb = (xcd >> 1) * (nbk / 4) + (idx % per) / hn;
+    } else {
+        e = blockIdx.x / tiles;
+        nb = (blockIdx.x % tiles) / nbk;
+        kb = (blockIdx.x % tiles) % nbk;
+    }
+    if (e >= p.E) return;
+    const int row0 = p.offsets[e], Me = p.offsets[e + 1] - row0;
+    const int stages = (Me + kStageM - 1) / kStageM;
+
+    // ---- copies: instruction i (0..3) of this wavefront moves rows 8 w + 2 i and 8 w + 2 i + 1 of a tile; lane L
+    // fills position L % 32 of row 8 w + 2 i + L / 32 with the chunk that belongs there
+    int rrow[4];
+    uint32_t chunkb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        rrow[i] = wave * 8 + 2 * i + h;
+        chunkb[i] = (uint32_t)(((lane & 31) ^ ((rrow[i] & 3) << 2)) << 4);
+    }
+    const unsigned char *ybase = (const unsigned char *)p.dy + ((int64_t)row0 * N + nb * kDwWTile) * 2;
+    const unsigned char *xbase = (const unsigned char *)p.x + (int64_t)kb * kDwWTile * 2;
+    const int32_t *mbase = row_map ? row_map + row0 : nullptr;
+    int32_t ids[8];                       // x rows of the wavefront's eight token rows of the stage addressed next
+    const unsigned char *ysrc[4], *xsrc[4];
+    auto load_ids = [&](int s) {
+        const int m0 = s * kStageM + wave * 8;
+        if (mbase) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) ids[r] = mbase[min(m0 + r, Me - 1)];
+        } else {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) ids[r] = row0 + m0 + r;
+        }
+    };
+    auto form_addresses = [&](int s) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = s * kStageM + rrow[i];
+            const bool valid = m < Me;
+            const int id = h ? ids[2 * i + 1] : ids[2 * i];
+            ysrc[i] = valid ? ybase + (uint64_t)(uint32_t)m * (uint32_t)(N * 2) + chunkb[i] : kDwZeroRow + chunkb[i];
+            xsrc[i] = valid ? xbase + (uint64_t)(uint32_t)id * (uint32_t)(K * 2) + chunkb[i] : kDwZeroRow + chunkb[i];
+        }
+    };
+    auto copy_one = [&](int buf, int i) {   // i = 0..3: Ys, 4..7: Xs
+        unsigned char *dst = smem + buf * kDwWStageB + (wave * 8 + 2 * (i & 3)) * kDwWRowB;
+        if (i < 4) copy16_to_lds(ysrc[i], dst);
+        else copy16_to_lds(xsrc[i - 4], dst + kDwWTileB);
+    };
+
+    // ---- operands: transposing reads, n columns 128 wn + 32 ms of Ys and k columns 64 wk + 32 nt of Xs
+    TrBase ta[4], tb[2];
+#pragma unroll
+    for (int ms = 0; ms < 4; ++ms) ta[ms] = tr_base_512(wn * 128 + ms * 32, lane);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        tb[nt] = tr_base_512(wk * 64 + nt * 32, lane);
+        tb[nt].lo += kDwWTileB;
+        tb[nt].hi += kDwWTileB;
+    }
+    struct Frags {
+        bf16x8 a[4], b[2];
+    };
+    // The transposing reads are written as asm: in front of a read the compiler can see it drains the asynchronous
+    // copies in flight (it cannot tell that they fill the other stage buffer).  The results are therefore waited for
+    // by hand: wait_frags() in front of the slice that multiplies them.
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)smem;
+    auto read_tr = [&](uint32_t base, const TrBase &t, auto off_c) -> bf16x8 {
+        constexpr int off = decltype(off_c)::value;
+        struct {
+            s16x4 lo, hi;
+        } v;
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v.lo) : "v"(base + (uint32_t)t.lo), "n"(off));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v.hi) : "v"(base + (uint32_t)t.hi), "n"(off));
+        return __builtin_bit_cast(bf16x8, v);
+    };
+    auto wait_frags = [&](Frags &f) {
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]));
+    };
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ms][nt][i] = 0.f;
+    // Slice j (16 token rows) of stage ks: the eight MFMAs on `cur`, behind each of the first six one operand of
+    // `nxt` (two transposing reads), in slices 0 and 1 behind every second MFMA one copy of the next stage.
+    auto slice = [&](Frags &cur, Frags &nxt, int ks, auto j_c, auto more_t) {
+        constexpr int j = decltype(j_c)::value;
+        const int buf = ks & 1;
+        const uint32_t base = lds0 + buf * kDwWStageB;
+        constexpr std::integral_constant<int, j * 16 * kDwWRowB> off{};
+        wait_frags(cur);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int ms = i >> 1, nt = i & 1;
+            acc[ms][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[ms], cur.b[nt], acc[ms][nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i < 4) nxt.a[i] = read_tr(base, ta[i], off);
+            else if (i < 6) nxt.b[i - 4] = read_tr(base, tb[i - 4], off);
+            if (decltype(more_t)::value && j < 2 && (i & 1)) copy_one(buf ^ 1, 4 * j + (i >> 1));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto stage_barrier = [&]() {   // own copies landed, own operand reads done; then everybody's
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
+
+    if (stages > 0) {
+        Frags last, f0, f1, f2, f3;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) last.a[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < 2; ++i) last.b[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        load_ids(0);
+        form_addresses(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) copy_one(0, i);
+        load_ids(1);
+        stage_barrier();
+        auto stage = [&](int ks, auto more_t) {
+            if (decltype(more_t)::value) {
+                form_addresses(ks + 1);   // from the ids loaded during the stage before
+                load_ids(ks + 2);
+            }
+            slice(last, f0, ks, std::integral_constant<int, 0>{}, more_t);
+            slice(f0, f1, ks, std::integral_constant<int, 1>{}, more_t);
+            slice(f1, f2, ks, std::integral_constant<int, 2>{}, more_t);
+            slice(f2, f3, ks, std::integral_constant<int, 3>{}, more_t);
+            stage_barrier();
+            last = f3;
+        };
+        for (int ks = 0; ks + 1 < stages; ++ks) stage(ks, std::true_type{});
+        stage(stages - 1, std::false_type{});
+        wait_frags(last);
+#pragma unroll
+        for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+                acc[ms][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(last.a[ms], last.b[nt], acc[ms][nt], 0, 0, 0);
+    }
+
+    // ---- epilogue: lane (k column m32 of tile nt, half h), register i -> weight row 32 ms + 8 (i / 4) + 4 h + i % 4.
+    // Every 32 x 32 tile turns through this wavefront's own piece of the first stage buffer (rows of 36 floats) and
+    // leaves as 16-byte (fp32) or 8-byte (bf16) pieces of whole 128-byte / 64-byte row segments.
+    constexpr int kORow = 36 * 4;
+    unsigned char *ot = smem + wave * (32 * kORow);
+    const int64_t obase = ((int64_t)e * N + nb * kDwWTile + wn * 128) * K + kb * kDwWTile + wk * 64;
+#pragma unroll
+    for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                *(float *)(ot + (8 * (i >> 2) + 4 * h + (i & 3)) * kORow + m32 * 4) = acc[ms][nt][i];
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
+                const int row = pass * 8 + (lane >> 3);
+                const f32x4 v4 = *(const f32x4 *)(ot + row * kORow + (lane & 7) * 16);
+                const int64_t o = obase + (int64_t)(ms * 32 + row) * K + nt * 32 + (lane & 7) * 4;
+                if (p.out_f32) {
+                    *(f32x4 *)((float *)p.out + o) = v4;
+                } else {
+                    u32x2 ob;
+                    ob[0] = (uint32_t)f32_to_bf16_hw(v4[0]) | ((uint32_t)f32_to_bf16_hw(v4[1]) << 16);
+                    ob[1] = (uint32_t)f32_to_bf16_hw(v4[2]) | ((uint32_t)f32_to_bf16_hw(v4[3]) << 16);
+                    *(u32x2 *)((uint16_t *)p.out + o) = ob;
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+}
+
 }  // namespace
 
 int launch_qgemm_dx(const GemmArgs &a, hipStream_t s)
@@ -382,6 +603,13 @@ int launch_grouped_dw(const void *dy, const void *x, const int32_t *row_map, con
     p.N = N;
     p.K = K;
     p.out_f32 = out_f32;
+    if (N % kDwWTile == 0 && K % kDwWTile == 0 && (int64_t)N * 2 < (1LL << 31) && (int64_t)K * 2 < (1LL << 31)) {
+        const int64_t total = (int64_t)E * (N / kDwWTile) * (K / kDwWTile);
+        static LdsLimitOnce once;
+        if (int rc = raise_lds_limit((const void *)grouped_dw_wide_kernel, once, "hipFuncSetAttribute(grouped dw)")) return rc;
+        grouped_dw_wide_kernel<<<dim3((unsigned)total), dim3(kBwThreads), 2 * kDwWStageB, s>>>(p, row_map);
+        return check_hip(hipGetLastError(), "grouped_dw_wide_kernel");
+    }
     grouped_dw_kernel<<<dim3((unsigned)grid), dim3(kBwThreads), 0, s>>>(p);
     return check_hip(hipGetLastError(), "grouped_dw_kernel");
 }

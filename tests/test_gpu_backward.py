@@ -66,7 +66,8 @@ def test_exact_integer_regime_bit_exact(q, oracle, N):
 
 
 @pytest.mark.parametrize("E,N,K,rows", [(3, 256, 384, (37, 0, 300)), (2, 128, 128, (1, 129)), (4, 384, 1024, (128, 256, 5, 64)),
-                                        (2, 256, 512, (70, 129)), (3, 512, 256, (0, 200, 63))])   # several tiles along n and k, an expert without rows
+                                        (2, 256, 512, (70, 129)), (3, 512, 256, (0, 200, 63)),    # several tiles along n and k, an expert without rows
+                                        (2, 512, 1024, (130, 65))])   # 2 x 4 tiles of 256 x 256 per expert: one per XCD, three stages and a ragged one
 def test_general_data_both_gradients(q, oracle, E, N, K, rows):
     seed = 8300 + N + K
     rng = np.random.default_rng(seed)
