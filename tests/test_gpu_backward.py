@@ -94,6 +94,9 @@ def test_general_data_both_gradients(q, oracle, E, N, K, rows):
     assert norm_err(dw.cpu().numpy(), dw_ref) <= TOL_F32
     dwb = q.qarl_grouped_dw(dy.cuda(), x.cuda(), _i32(off), E, row_map=_i32(rm))
     assert norm_err_bf16(dwb.float().cpu().numpy(), dw_ref) <= TOL_BF16
+    # without a row map the activation rows are the problem's rows themselves
+    dw_id = q.qarl_grouped_dw(dy.cuda(), x.cuda(), _i32(off), E, out_dtype=q.QARL_OUT_F32)
+    assert norm_err(dw_id.cpu().numpy(), oracle.grouped_dw(np_bits(dy), np_bits(x), off, E)) <= TOL_F32
     # the adjoint identity on the GPU's own results: <dY, Y> = <dX, X> = <dW, What>
     y = q.qarl_qgemm_grouped(qw, x.cuda(), _i32(off), M, row_map=_i32(rm), out_dtype=q.QARL_OUT_F32).double()
     a = float((dy.cuda().double() * y).sum())
