@@ -227,20 +227,22 @@ __global__ __launch_bounds__(256) void target_logit_kernel(const uint16_t *__res
     if (lane == 0) tgt[t] = s * inv_temp;
 }
 
-// Merge the per-block partials of one token and emit the log-prob.  64 tokens per workgroup; four
-// threads per token each fold every fourth block into a running (max, sum), and the four meet in LDS in
-// a fixed order, so the result does not depend on scheduling.
+// Merge the per-block partials of one token and emit the log-prob.  16 tokens per workgroup; sixteen
+// threads per token each fold every sixteenth block into a running (max, sum) (a chain of n_blocks / 16
+// dependent steps: with four threads per token the launch took 88 us at 594 blocks), and the sixteen meet in
+// LDS in a fixed order, so the result does not depend on scheduling.
+constexpr int kFinTokens = 16, kFinSlices = 16;
 __global__ __launch_bounds__(256) void lse_finalize_kernel(const float *__restrict__ pmax,
                                                            const float *__restrict__ psum,
                                                            const float *__restrict__ tgt, int T, int n_blocks,
                                                            float *__restrict__ logprob)
 {
-    __shared__ float s_m[4][64], s_s[4][64];
-    const int tl = threadIdx.x & 63, slice = threadIdx.x >> 6;
-    const int t = blockIdx.x * 64 + tl;
+    __shared__ float s_m[kFinSlices][kFinTokens], s_s[kFinSlices][kFinTokens];
+    const int tl = threadIdx.x % kFinTokens, slice = threadIdx.x / kFinTokens;
+    const int t = blockIdx.x * kFinTokens + tl;
     float m = -INFINITY, s = 0.f;
     if (t < T) {
-        for (int b = slice; b < n_blocks; b += 4) {
+        for (int b = slice; b < n_blocks; b += kFinSlices) {
             const float mb = pmax[(int64_t)b * T + t], sb = psum[(int64_t)b * T + t];
             if (mb > m) {
                 s = s * expf(m - mb) + sb;   // exp(-inf) = 0 on the first block
@@ -254,10 +256,12 @@ __global__ __launch_bounds__(256) void lse_finalize_kernel(const float *__restri
     s_s[slice][tl] = s;
     __syncthreads();
     if (slice == 0 && t < T) {
-        float mm = fmaxf(fmaxf(s_m[0][tl], s_m[1][tl]), fmaxf(s_m[2][tl], s_m[3][tl]));
+        float mm = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < kFinSlices; ++q) mm = fmaxf(mm, s_m[q][tl]);
         double ss = 0.0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < kFinSlices; ++q)
             if (s_m[q][tl] > -INFINITY) ss += (double)s_s[q][tl] * (double)expf(s_m[q][tl] - mm);
         logprob[t] = tgt[t] - (mm + (float)log(ss));
     }
@@ -305,7 +309,8 @@ int launch_logprob(const void *h, const void *wlm, const int32_t *target, int T,
     lmhead_lse_kernel<<<dim3((unsigned)grid), dim3(kLThreads), kLLds, s>>>(p);
     rc = check_hip(hipGetLastError(), "lmhead_lse_kernel");
     if (rc) return rc;
-    lse_finalize_kernel<<<dim3((T + 63) / 64), dim3(256), 0, s>>>(p.pmax, p.psum, tgt, T, p.n_blocks, logprob);
+    lse_finalize_kernel<<<dim3((T + kFinTokens - 1) / kFinTokens), dim3(kFinTokens * kFinSlices), 0, s>>>(p.pmax, p.psum, tgt, T, p.n_blocks,
+                                                                                                           logprob);
     return check_hip(hipGetLastError(), "lse_finalize_kernel");
 }
 
