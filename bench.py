@@ -374,7 +374,33 @@ def main():
                 "gate_up_ms": round(ms_gud, 4), "down_ms": round(ms_dnd, 4),
                 "TFLOP/s": round(fl_d / (ms_gud + ms_dnd) / 1e9, 1),
                 "frac_mfma_bf16": round(fl_d / (ms_gud + ms_dnd) / 1e9 / MFMA_BF16_PEAK_TF, 4)}
-            del qgud, qdnd, xd, ad, yd, wsd
+            # the same MLP at a decode batch of 64 tokens on the weight-streaming path: gate_up with K = 4096 as it is;
+            # the K = 12288 down projection as six K-chunks of 2048, chunk c = expert c, every token listing all six,
+            # the activations read as [6 T][2048], the combine (unit weights) adding the six fp32 partial products
+            Tdd, KC = 64, 2048
+            Cd = Id // KC
+            dnd2 = synth.normal_bf16((1, Hd, Id), 0.02, seed=71, device=dev)
+            qdnc = q.qarl_quantize_weights(dnd2.view(Hd, Cd, KC).permute(1, 0, 2).contiguous())
+            del dnd2
+            xdd = xd[:Tdd].contiguous()
+            offdd = torch.tensor([0, Tdd], dtype=torch.int32, device=dev)
+            add = torch.empty((Tdd, Id), dtype=torch.bfloat16, device=dev)
+            ydd = torch.empty((Tdd, Hd), dtype=torch.bfloat16, device=dev)
+            idsd = torch.arange(Cd, dtype=torch.int32, device=dev).repeat(Tdd, 1).contiguous()
+            onesd = torch.ones((Tdd, Cd), dtype=torch.float32, device=dev)
+            wsdd = torch.empty((max(q.qarl_qgemm_workspace_bytes(qdnc, Tdd * Cd, Tdd * Cd, q.QARL_EPI_COMBINE), 16),),
+                               dtype=torch.uint8, device=dev)
+            ms_gudd = timed(lambda: q.qarl_qgemm_grouped(qgud, xdd, offdd, Tdd, epilogue=q.QARL_EPI_SILU_MUL, out=add,
+                                                         path=q.QARL_PATH_DECODE, ws=wsd), 20, 3)
+            ms_dndd = timed(lambda: q.qarl_qgemm_routed(qdnc, add.view(Tdd * Cd, KC), idsd, Tdd, Cd, False,
+                                                        epilogue=q.QARL_EPI_COMBINE, combine_w=onesd, out=ydd, ws=wsdd), 20, 3)
+            wb_gu, wb_dn = weight_bytes_w4a16(1, 2 * Id, Hd), weight_bytes_w4a16(1, Hd, Id)
+            extra["dense_mlp_w4a16_4096x12288_decode_64tok"] = {
+                "gate_up_ms": round(ms_gudd, 4), "down_ms": round(ms_dndd, 4),
+                "gate_up_weight_GB/s": round(wb_gu / ms_gudd / 1e6, 1), "down_weight_GB/s": round(wb_dn / ms_dndd / 1e6, 1),
+                "frac_hbm": round((wb_gu + wb_dn) / (ms_gudd + ms_dndd) / 1e6 / HBM_PEAK_GBS, 4),
+                "note": "down = 6 K-chunks as experts in routed mode + combine; both weights (75 MB) fit the last-level cache"}
+            del qgud, qdnd, qdnc, xd, xdd, ad, add, yd, ydd, wsd, wsdd
 
         if on("fp8"):
             # FP8 W8A8 layer at 256 and 8192 tokens: the whole layer, and the two grouped GEMM launches on their own

@@ -411,3 +411,27 @@ def test_dense_mlp_second_model_shape(q, oracle):
     assert flip_fraction(np_bits(a_rows), a_ref_bits) <= MAX_FLIPS
     y_ref = oracle.qgemm_w4a16(np_bits(a_rows), dnc, dns, sub)          # on the GPU's own a
     assert norm_err(y[torch.tensor(rows, device="cuda")].cpu().numpy(), y_ref) <= TOL_F32
+
+
+def test_dense_decode_down_projection_as_k_chunks(q, oracle):
+    """The K = 12288 down projection of the dense model at a decode batch, on the weight-streaming path: the
+    contraction is cut into six chunks of 2048, chunk c of the weight is expert c (W'[c][n][k'] = W[n][2048 c + k'];
+    scale groups of 128 never straddle a chunk, so codes and scales are those of W), the activation matrix
+    [T][12288] is read as [6 T][2048] (row 6 t + c = chunk c of token t = the pair id of token t, slot c), every
+    token lists all six experts, and the combine epilogue with unit weights adds the six fp32 partial products in
+    chunk order.  Against the oracle's dense product of the unchunked tensors."""
+    H2, I2, Td, C, KC = 4096, 12288, 40, 6, 2048
+    dn = synth.normal_bf16((1, H2, I2), 0.02, seed=701, device="cuda")
+    a = synth.normal_bf16((Td, I2), 1.0, seed=705, device="cuda")
+    dnc, dns = oracle.quantize_int4(np_bits(dn))
+    ref = oracle.qgemm_w4a16(np_bits(a), dnc, dns, np.array([0, Td], dtype=np.int32))
+    qc = q.qarl_quantize_weights(dn.view(H2, C, KC).permute(1, 0, 2).contiguous())          # E = 6, N = 4096, K = 2048
+    assert np.array_equal(unblock_int4(qc.codes, C, H2, KC), dnc.reshape(H2, C, KC // 8).transpose(1, 0, 2))
+    assert np.array_equal(np_bits(qc.scales).reshape(C, H2, KC // 128), dns.reshape(H2, C, KC // 128).transpose(1, 0, 2))
+    ids = torch.arange(C, dtype=torch.int32, device="cuda").repeat(Td, 1).contiguous()
+    ones = torch.ones((Td, C), dtype=torch.float32, device="cuda")
+    out = q.qarl_qgemm_routed(qc, a.view(Td * C, KC), ids, Td, C, False, epilogue=q.QARL_EPI_COMBINE, combine_w=ones)
+    assert out.shape == (Td, H2)
+    assert norm_err_bf16(out.float().cpu().numpy(), ref) <= TOL_BF16
+    ref_bits = np_bits(torch.tensor(ref, dtype=torch.float64).to(torch.bfloat16))
+    assert flip_fraction(np_bits(out), ref_bits) <= MAX_FLIPS
