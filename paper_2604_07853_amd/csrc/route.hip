@@ -67,8 +67,11 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(const uint16_
                                                                   int E, int topk, int renorm,
                                                                   int32_t *__restrict__ ids,
                                                                   float *__restrict__ wts,
-                                                                  int32_t *__restrict__ counts)
+                                                                  int32_t *__restrict__ counts,
+                                                                  int32_t *__restrict__ zero_me, int n_zero)
 {
+    // large batches: the per-expert counters the counting kernel behind this one adds to start at zero (saves a launch)
+    if (blockIdx.x == 0 && (int)threadIdx.x < n_zero) zero_me[threadIdx.x] = 0;
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * (kRouteThreads / 64) + (threadIdx.x >> 6);
     if (t >= T) return;
@@ -320,7 +323,7 @@ int launch_route_only(const void *logits, int T, int E, int topk, int renorm, in
 {
     const int per_block = kRouteThreads / 64;
     route_topk_kernel<<<dim3((T + per_block - 1) / per_block), dim3(kRouteThreads), 0, s>>>(
-        (const uint16_t *)logits, T, E, topk, renorm, ids, w, nullptr);
+        (const uint16_t *)logits, T, E, topk, renorm, ids, w, nullptr, nullptr, 0);
     return check_hip(hipGetLastError(), "route_topk_kernel");
 }
 
@@ -331,18 +334,22 @@ int launch_route(const void *logits, int T, int E, int topk, int renorm, int32_t
     const int64_t n_pairs = (int64_t)T * topk;
     if (T > 0 && T <= kSmallMaxT && n_pairs <= kSmallMaxPairs) {
         route_topk_kernel<<<dim3((T + per_block - 1) / per_block), dim3(kRouteThreads), 0, s>>>(
-            (const uint16_t *)logits, T, E, topk, renorm, ids, w, nullptr);
+            (const uint16_t *)logits, T, E, topk, renorm, ids, w, nullptr, nullptr, 0);
         int rc = check_hip(hipGetLastError(), "route_topk_kernel");
         if (rc) return rc;
         group_small_kernel<<<dim3(1), dim3(kSmallThreads), 0, s>>>(ids, T, E, topk, counts, offsets, pairs, tokens);
         return check_hip(hipGetLastError(), "group_small_kernel");
     }
-    zero_i32_kernel<<<dim3((E + 255) / 256), dim3(256), 0, s>>>(counts, E);
-    int rc = check_hip(hipGetLastError(), "zero_i32_kernel");
-    if (rc) return rc;
+    int rc;
+    if (T == 0) {   // no router launch to zero the counters: the grouping below then writes counts = 0, offsets = 0
+        zero_i32_kernel<<<dim3((E + 255) / 256), dim3(256), 0, s>>>(counts, E);
+        rc = check_hip(hipGetLastError(), "zero_i32_kernel");
+        if (rc) return rc;
+    }
     if (T > 0) {
+        static_assert(kRouteThreads >= 256, "the router's first workgroup zeroes up to 256 expert counters");
         route_topk_kernel<<<dim3((T + per_block - 1) / per_block), dim3(kRouteThreads), 0, s>>>(
-            (const uint16_t *)logits, T, E, topk, renorm, ids, w, nullptr);
+            (const uint16_t *)logits, T, E, topk, renorm, ids, w, nullptr, counts, E);
         rc = check_hip(hipGetLastError(), "route_topk_kernel");
         if (rc) return rc;
         count_experts_kernel<<<dim3(kCountBlocks), dim3(kCountThreads), 0, s>>>(ids, (int)n_pairs, E, counts);
